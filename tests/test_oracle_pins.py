@@ -1,0 +1,272 @@
+"""Pins for the CPU oracle: each test checks it against something other than
+itself - a hand-computed fixture, a closed form, a brute-force expansion, a
+library routine on a special case, or an algebraic invariant (CPU only)."""
+import itertools
+
+import numpy as np
+import pytest
+import torch
+
+from ebs_workloads import draw_levels
+from golden_io import read_sections
+
+BITS = [(kw, ka) for kw in range(1, 5) for ka in range(1, 5)]
+
+
+def _rand(seed, N, C, H, W, K, R, S, kw, ka):
+    rng = np.random.default_rng(seed)
+    q = draw_levels(rng, (K, R, S, C), kw)
+    a = draw_levels(rng, (N, H, W, C), ka)
+    return a, q
+
+
+# ---------------------------------------------------------------- fixture
+def test_hand_worked_example_matrix_form(oracle_mod):
+    """Sec. 4.3 worked example (2x3 weights, 3x2 activations, 2 digits each) with
+    hand-computed B_w, B_x, P and O."""
+    g = read_sections("bd_worked_example_2x3_3x2.txt")
+    Wm, Xm = g["W"], g["X"]
+    # as a 1x1 convolution: c_o = 2, c_i = 3, two output positions
+    q = Wm.reshape(2, 1, 1, 3).astype(np.uint8)
+    a = Xm.T.reshape(1, 1, 2, 3).astype(np.uint8)
+    O, P = oracle_mod.bd_matrix_form(a, q, 2, 2)
+    assert np.array_equal(P, g["P"])
+    assert np.array_equal(O.reshape(2, 2).T, g["O"])
+    O2, _ = oracle_mod.bd_matrix_form(a, q, 2, 2, explicit_lambda=True)
+    assert np.array_equal(O2, O)
+    # the C routines on the same numbers
+    assert np.array_equal(oracle_mod.conv2d_levels(a, q).reshape(2, 2).T, g["O"])
+    acc, planes = oracle_mod.bitplane_conv(a, q, 2, 2, return_planes=True)
+    assert np.array_equal(acc.reshape(2, 2).T, g["O"])
+    # planes[n,oh,ow,k,m,kk] == P[k*M+m, j*K+kk]
+    for j in range(2):
+        for i in range(2):
+            for m in range(2):
+                for kk in range(2):
+                    assert planes[0, 0, j, i, m, kk] == g["P"][2 * i + m, 2 * j + kk]
+    assert np.array_equal(g["W"] @ g["X"], g["O"])
+
+
+def test_hand_fixture_decomposition_identity():
+    """Eq. 12: W = Lambda_w B_w and X = B_x Lambda_x^T on the fixture's digits."""
+    g = read_sections("bd_worked_example_2x3_3x2.txt")
+    Lw = np.kron(np.eye(2, dtype=np.int64), np.array([[1, 2]]))
+    assert np.array_equal(Lw @ g["B_w"], g["W"])
+    Lx = np.kron(np.eye(2, dtype=np.int64), np.array([[1, 2]]))
+    assert np.array_equal(g["B_x"] @ Lx.T, g["X"])
+    assert np.array_equal(g["B_w"] @ g["B_x"], g["P"])
+
+
+# ---------------------------------------------------------------- Eq. 2 identity (brute force)
+@pytest.mark.parametrize("kw,ka", BITS)
+def test_direct_equals_bitplane_bruteforce(oracle_mod, kw, ka):
+    geos = [  # N, C, H, W, K, R, S, stride, pad
+        (1, 5, 4, 5, 3, 3, 3, 1, 1),
+        (2, 33, 5, 4, 2, 3, 3, 2, 1),
+        (1, 16, 6, 6, 4, 1, 1, 1, 0),
+        (1, 7, 7, 6, 2, 3, 2, 2, 0),
+        (1, 3, 5, 5, 2, 5, 5, 1, 2),
+    ]
+    for gi, (N, C, H, W, K, R, S, st, pad) in enumerate(geos):
+        a, q = _rand(1000 + 17 * gi + 4 * kw + ka, N, C, H, W, K, R, S, kw, ka)
+        d = oracle_mod.conv2d_levels(a, q, st, pad)
+        b = oracle_mod.bitplane_conv(a, q, kw, ka, st, pad)
+        assert d.shape == b.shape
+        assert np.array_equal(d, b), (kw, ka, gi)
+
+
+@pytest.mark.parametrize("kw,ka", [(1, 1), (2, 3), (4, 4), (3, 1)])
+def test_matrix_form_equals_direct(oracle_mod, kw, ka):
+    N, C, H, W, K, R, S, st, pad = 2, 6, 5, 5, 3, 3, 3, 2, 1
+    a, q = _rand(77 + kw * 5 + ka, N, C, H, W, K, R, S, kw, ka)
+    O, P = oracle_mod.bd_matrix_form(a, q, kw, ka, st, pad)
+    d = oracle_mod.conv2d_levels(a, q, st, pad)
+    assert np.array_equal(O, d)
+    OH, OW = oracle_mod.out_dims(H, W, R, S, st, pad)
+    assert P.shape == (K * kw, N * OH * OW * ka)          # c_o M x n K  (Sec. 4.3)
+    acc, planes = oracle_mod.bitplane_conv(a, q, kw, ka, st, pad, return_planes=True)
+    # P[(i,m),(j,k)] == planes[j][i][m][k]
+    Pp = planes.reshape(N * OH * OW, K, kw, ka).transpose(1, 2, 0, 3).reshape(K * kw, -1)
+    assert np.array_equal(Pp, P)
+    O2, _ = oracle_mod.bd_matrix_form(a, q, kw, ka, st, pad, explicit_lambda=True)
+    assert np.array_equal(O2, d)
+
+
+# ---------------------------------------------------------------- library special case
+@pytest.mark.parametrize("geo", [
+    (2, 19, 9, 7, 5, 3, 3, 1, 1), (1, 64, 8, 8, 8, 3, 3, 2, 1), (2, 8, 6, 9, 4, 1, 1, 1, 0),
+    (1, 4, 9, 9, 3, 5, 3, 2, 2), (1, 10, 7, 7, 2, 3, 3, 3, 0), (3, 16, 8, 8, 16, 3, 3, 1, 1),
+])
+def test_direct_equals_float64_library_conv(oracle_mod, geo):
+    """Integer levels are exactly representable, every partial sum < 2^53, so the
+    float64 library convolution is exact and must agree digit for digit."""
+    N, C, H, W, K, R, S, st, pad = geo
+    a, q = _rand(hash(geo) % 100000, N, C, H, W, K, R, S, 4, 4)
+    ref = torch.nn.functional.conv2d(
+        torch.from_numpy(a.astype(np.float64)).permute(0, 3, 1, 2),
+        torch.from_numpy(q.astype(np.float64)).permute(0, 3, 1, 2), stride=st, padding=pad)
+    ref = ref.permute(0, 2, 3, 1).numpy()
+    d = oracle_mod.conv2d_levels(a, q, st, pad)
+    assert d.shape == ref.shape
+    assert np.array_equal(d.astype(np.float64), ref)
+
+
+def test_1x1_is_integer_matmul(oracle_mod):
+    N, C, H, W, K = 3, 70, 4, 5, 11
+    a, q = _rand(5, N, C, H, W, K, 1, 1, 3, 4)
+    d = oracle_mod.conv2d_levels(a, q, 1, 0)
+    ref = a.reshape(-1, C).astype(np.int64) @ q.reshape(K, C).astype(np.int64).T
+    assert np.array_equal(d.reshape(-1, K), ref)
+
+
+# ---------------------------------------------------------------- closed forms
+@pytest.mark.parametrize("kw,ka", [(1, 1), (2, 2), (4, 3), (4, 4)])
+def test_all_max_levels_closed_form(oracle_mod, kw, ka):
+    N, C, H, W, K = 1, 12, 6, 7, 3
+    top = (2 ** kw - 1) * (2 ** ka - 1)
+    a = np.full((N, H, W, C), 2 ** ka - 1, np.uint8)
+    q = np.full((K, 3, 3, C), 2 ** kw - 1, np.uint8)
+    d = oracle_mod.conv2d_levels(a, q, 1, 1)
+    assert d.shape == (N, H, W, K)
+    assert np.all(d[:, 1:-1, 1:-1, :] == 9 * C * top)      # interior: all 9 taps
+    for (h, w) in [(0, 0), (0, W - 1), (H - 1, 0), (H - 1, W - 1)]:
+        assert np.all(d[:, h, w, :] == 4 * C * top)        # corner: 4 taps
+    assert np.all(d[:, 0, 1:-1, :] == 6 * C * top)         # edge: 6 taps
+    assert np.all(d[:, 1:-1, 0, :] == 6 * C * top)
+    # stride 2, pad 1 on 6x7 -> 3x4; output (0,0) sees taps r,s in {1,2} -> 4 taps
+    d2 = oracle_mod.conv2d_levels(a, q, 2, 1)
+    assert d2.shape == (N, 3, 4, K)
+    assert np.all(d2[:, 0, 0, :] == 4 * C * top)
+    assert np.all(d2[:, 1, 1, :] == 9 * C * top)
+    assert np.all(d2[:, 0, 1, :] == 6 * C * top)
+    # the widest ResNet-18 case stays far below 2^31
+    assert 512 * 9 * 15 * 15 == 1036800
+
+
+def test_single_nonzero_weight_picks_shifted_input(oracle_mod):
+    """q[k0,r0,s0,c0] = v, all else 0  =>  acc[n,k0,oh,ow] = v * a_pad[n, oh*st+r0-pad, ow*st+s0-pad, c0]."""
+    N, C, H, W, K, R, S = 2, 5, 7, 6, 4, 3, 3
+    rng = np.random.default_rng(11)
+    a = draw_levels(rng, (N, H, W, C), 4)
+    for (k0, r0, s0, c0, v, st, pad) in [(1, 0, 2, 3, 7, 1, 1), (3, 2, 0, 0, 15, 2, 1), (0, 1, 1, 4, 1, 1, 0),
+                                          (2, 0, 0, 2, 5, 2, 2)]:
+        q = np.zeros((K, R, S, C), np.uint8)
+        q[k0, r0, s0, c0] = v
+        d = oracle_mod.conv2d_levels(a, q, st, pad)
+        OH, OW = oracle_mod.out_dims(H, W, R, S, st, pad)
+        ap = np.zeros((N, H + 2 * pad, W + 2 * pad, C), np.int64)
+        ap[:, pad:pad + H, pad:pad + W] = a
+        for oh in range(OH):
+            for ow in range(OW):
+                exp = v * ap[:, oh * st + r0, ow * st + s0, c0]
+                assert np.array_equal(d[:, oh, ow, k0], exp)
+        mask = np.ones(K, bool)
+        mask[k0] = False
+        assert np.all(d[..., mask] == 0)
+
+
+def test_output_geometry_matches_library(oracle_mod):
+    for H, W, R, S, st, pad in itertools.product([5, 8, 9], [6, 7], [1, 3], [1, 3], [1, 2, 3], [0, 1]):
+        if pad >= R or pad >= S:
+            continue
+        t = torch.nn.functional.conv2d(torch.zeros(1, 1, H, W), torch.zeros(1, 1, R, S), stride=st, padding=pad)
+        assert tuple(t.shape[2:]) == oracle_mod.out_dims(H, W, R, S, st, pad)
+
+
+# ---------------------------------------------------------------- invariants
+def test_linearity_in_weights_and_activations(oracle_mod):
+    N, C, H, W, K = 1, 9, 6, 6, 3
+    rng = np.random.default_rng(3)
+    a1 = draw_levels(rng, (N, H, W, C), 2)
+    a2 = draw_levels(rng, (N, H, W, C), 2)
+    q1 = draw_levels(rng, (K, 3, 3, C), 2)
+    q2 = draw_levels(rng, (K, 3, 3, C), 2)
+    f = lambda a, q: oracle_mod.conv2d_levels(a, q, 1, 1).astype(np.int64)
+    assert np.array_equal(f(a1 + a2, q1), f(a1, q1) + f(a2, q1))
+    assert np.array_equal(f(a1, q1 + q2), f(a1, q1) + f(a1, q2))
+    assert np.array_equal(f(3 * a1, q1), 3 * f(a1, q1))
+
+
+def test_full_convolution_checksum(oracle_mod):
+    """stride 1, pad = R-1: every (weight tap, pixel) pair meets exactly once, so
+    sum(acc) = sum_c (sum of weights in c) * (sum of activations in c)."""
+    N, C, H, W, K, R, S = 2, 6, 5, 4, 3, 3, 3
+    a, q = _rand(21, N, C, H, W, K, R, S, 3, 4)
+    d = oracle_mod.conv2d_levels(a, q, 1, R - 1).astype(np.int64)
+    qs = q.astype(np.int64).sum(axis=(0, 1, 2))
+    as_ = a.astype(np.int64).sum(axis=(0, 1, 2))
+    assert d.sum() == int((qs * as_).sum())
+
+
+def test_transposed_filter_is_detected(oracle_mod):
+    """An asymmetric filter gives a different answer when r and s are swapped, so a
+    transposed-operand mistake cannot hide: check against an explicit shift-sum."""
+    N, C, H, W, K = 1, 2, 5, 6, 1
+    rng = np.random.default_rng(8)
+    a = draw_levels(rng, (N, H, W, C), 3)
+    q = np.zeros((K, 2, 3, C), np.uint8)
+    q[0, 0, 2, 0] = 3
+    q[0, 1, 0, 1] = 2
+    d = oracle_mod.conv2d_levels(a, q, 1, 0)       # OH=4, OW=4
+    exp = 3 * a[0, 0:4, 2:6, 0].astype(np.int64) + 2 * a[0, 1:5, 0:4, 1].astype(np.int64)
+    assert np.array_equal(d[0, :, :, 0], exp)
+
+
+def test_point_matches_full(oracle_mod):
+    N, C, H, W, K, R, S, st, pad = 2, 20, 9, 8, 6, 3, 3, 2, 1
+    a, q = _rand(31, N, C, H, W, K, R, S, 4, 2)
+    d = oracle_mod.conv2d_levels(a, q, st, pad)
+    rng = np.random.default_rng(0)
+    for _ in range(50):
+        n, oh, ow, k = (int(rng.integers(0, s)) for s in d.shape)
+        assert oracle_mod.conv2d_point(a, q, st, pad, n, k, oh, ow) == d[n, oh, ow, k]
+
+
+# ---------------------------------------------------------------- stage-2 special cases
+def test_one_bit_is_plain_binary_conv(oracle_mod):
+    """(M,K) = (1,1): the result is the bitcount of the AND alone."""
+    N, C, H, W, K = 1, 40, 5, 5, 2
+    a, q = _rand(41, N, C, H, W, K, 3, 3, 1, 1)
+    acc, planes = oracle_mod.bitplane_conv(a, q, 1, 1, 1, 1, return_planes=True)
+    assert np.array_equal(acc, planes[..., 0, 0])
+    assert np.array_equal(acc, oracle_mod.conv2d_levels(a, q, 1, 1))
+
+
+def test_all_one_activations_sum_weights(oracle_mod):
+    """K = 1 activations all 1 and no padding: acc = sum of the weight levels."""
+    C, K = 13, 3
+    rng = np.random.default_rng(2)
+    q = draw_levels(rng, (K, 3, 3, C), 4)
+    a = np.ones((1, 5, 5, C), np.uint8)
+    d = oracle_mod.conv2d_levels(a, q, 1, 0)
+    for k in range(K):
+        assert np.all(d[..., k] == q[k].astype(np.int64).sum())
+
+
+# ---------------------------------------------------------------- epilogue
+def test_dequant_identity_and_values(oracle_mod):
+    acc = np.array([[0, 1, -5, 1036800], [7, 8, 9, 10]], dtype=np.int32)
+    out = oracle_mod.dequant(acc, np.float32(1.0))
+    assert out.dtype == np.float32 and np.array_equal(out, acc.astype(np.float32))
+    out = oracle_mod.dequant(acc, np.float32(0.5), np.float32(0.25))
+    assert np.array_equal(out, (acc * 0.5 + 0.25).astype(np.float32))   # exact in binary
+    sc = np.array([0.1, 0.2, 0.3, 0.4], np.float32)
+    of = np.array([1.0, -1.0, 0.5, 0.0], np.float32)
+    out = oracle_mod.dequant(acc, sc, of, per_channel=True)
+    exp = (sc.astype(np.float64) * acc + of.astype(np.float64)).astype(np.float32)
+    assert np.array_equal(out, exp)
+    # constant arrays == per-layer broadcast
+    c = oracle_mod.dequant(acc, np.full(4, 0.1, np.float32), np.full(4, 0.3, np.float32), per_channel=True)
+    l = oracle_mod.dequant(acc, np.float32(0.1), np.float32(0.3))
+    assert np.array_equal(c, l)
+
+
+def test_op_count_formula():
+    """Sec. 4.3 complexities: s*n*c_o*M*K ANDs (and as many counted bits)."""
+    from ebs_workloads import config_cases
+    c = config_cases(3)[0]   # 64->64 @56, N=64, (1,1)
+    L = c.layer
+    s, n, co = L.C * 9, L.N * 56 * 56, L.K
+    assert c.binary_ops == 2 * s * n * co * 1 * 1
+    c44 = [x for x in config_cases(3) if x.layer_index == 0 and (x.k_w, x.k_a) == (4, 4)][0]
+    assert c44.binary_ops == 16 * c.binary_ops
