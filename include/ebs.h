@@ -1,0 +1,150 @@
+/*
+ * libebs - mixed-precision convolution by binary decomposition on MI355X (gfx950).
+ *
+ * The operation (paper Sec. 3, Eq. 2; Sec. 4.3, Eq. 12-15): a convolution of
+ * k_w-bit unsigned weight levels with k_a-bit unsigned activation levels is
+ * computed from the bit planes of both operands: every (weight plane i,
+ * activation plane j) pair is multiplied with bitwise AND + bitcount, and the
+ * partial products are recombined with the power-of-two factors 2^(i+j).  The
+ * layer's affine terms (clip parameter, level spacing, batch-norm folding;
+ * Sec. 4.3 "Complexities", first paragraph) are applied after the integer
+ * result as out = scale * acc + offset.
+ *
+ * Conventions common to every call
+ *  - All data pointers are DEVICE pointers (HBM) owned by the caller; the
+ *    library allocates nothing, frees nothing and keeps no state between
+ *    calls.  Buffers must be 16-byte aligned.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Every call only enqueues kernels on that stream and returns; results are
+ *    valid once the stream has been synchronised by the caller.
+ *  - Return value: EBS_OK (0) or a negative ebs_status.  Argument errors are
+ *    detected on the host before anything is enqueued.  Nothing throws or
+ *    aborts across this boundary.
+ *  - Levels: uint8, one level per byte.  Activations are NHWC
+ *    a[n][h][w][c]; weights are KRSC q[k][r][s][c].  Only the low k bits of a
+ *    level are used (level & (2^k - 1)); plane m is bit m, plane 0 the LSB.
+ *  - Outputs are NHWC: acc[n][oh][ow][k] with
+ *    OH = floor((H + 2*pad - R)/stride) + 1 and OW likewise; taps outside the
+ *    image contribute zero (activation level 0 is the real value 0).
+ *  - Bitwidths: 1 <= k_w, k_a <= 4.
+ *  - Packed buffers are opaque: their size comes from the *_bytes() calls and
+ *    their content is only meaningful to ebs_mixed_conv2d of the same library
+ *    version.
+ */
+#ifndef EBS_H
+#define EBS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    EBS_OK = 0,
+    EBS_ERR_NULL = -1,        /* a required pointer is NULL                         */
+    EBS_ERR_BITWIDTH = -2,    /* k_w or k_a outside [1, 4]                          */
+    EBS_ERR_SHAPE = -3,       /* non-positive extent, empty output, pad >= filter,
+                                 or a tensor with 2^31 or more elements            */
+    EBS_ERR_ALIGN = -4,       /* a buffer is not 16-byte aligned                    */
+    EBS_ERR_UNSUPPORTED = -5, /* valid request this build has no kernel for         */
+    EBS_ERR_HIP = -6,         /* the HIP runtime refused a launch                   */
+    EBS_ERR_LEVEL_RANGE = -7  /* ebs_check_levels found a level >= 2^bits           */
+} ebs_status;
+
+/* Library version (major*10000 + minor*100 + patch). */
+int ebs_version(void);
+
+/* Static, human-readable name of a status code. */
+const char *ebs_status_string(int status);
+
+/*
+ * Size in bytes of the packed bit-plane form of a weight tensor (the binary
+ * matrix B_w of Eq. 12/15: k_w planes, channel bits packed into 32-bit words)
+ * and of an activation tensor (B_x, k_a planes).  Return 0 on invalid
+ * arguments.
+ */
+size_t ebs_packed_weights_bytes(int K, int C, int R, int S, int k_w);
+size_t ebs_packed_activations_bytes(int N, int H, int W, int C, int k_a);
+
+/*
+ * Weight decomposition W = Lambda_w B_w (Eq. 12, 15): split the KRSC levels
+ * into k_w bit planes and pack input-channel bits into 32-bit words.  Done
+ * once per layer (offline in the paper's deployment flow).
+ *   levels_krsc : in,  device, K*R*S*C bytes
+ *   packed      : out, device, ebs_packed_weights_bytes(...) bytes
+ */
+int ebs_pack_weights(const uint8_t *levels_krsc, int K, int C, int R, int S, int k_w,
+                     void *packed, void *stream);
+
+/*
+ * Activation decomposition X = B_x Lambda_x^T (Eq. 12, 15): split the NHWC
+ * levels into k_a bit planes, channel bits packed into 32-bit words.  Runs
+ * once per layer invocation.
+ *   levels_nhwc : in,  device, N*H*W*C bytes
+ *   packed      : out, device, ebs_packed_activations_bytes(...) bytes
+ */
+int ebs_pack_activations(const uint8_t *levels_nhwc, int N, int H, int W, int C, int k_a,
+                         void *packed, void *stream);
+
+/*
+ * The mixed-precision convolution (Eq. 2 applied to every output; stage 1
+ * P = B_w B_x by AND + bitcount, Eq. 13; stage 2 o = sum_i sum_j 2^(i+j) p_ij,
+ * Eq. 14, fused into the same kernel) followed by the affine epilogue.
+ *   packed_act : in, device, from ebs_pack_activations(N,H,W,C,k_a)
+ *   packed_wgt : in, device, from ebs_pack_weights(K,C,R,S,k_w)
+ *   scale      : in, device, 1 float (per_channel == 0) or K floats
+ *   offset     : in, device, same count as scale, or NULL for zero
+ *   acc_out    : out, device, int32 [N][OH][OW][K], exact integer result
+ *   out_f32    : out, device, float [N][OH][OW][K] = scale*acc + offset
+ *                (one fused multiply-add in fp32); may be NULL to skip it
+ * Groups = 1, dilation = 1, square stride, symmetric zero padding, pad < R,S.
+ */
+int ebs_mixed_conv2d(const void *packed_act, const void *packed_wgt,
+                     int N, int C, int H, int W, int K, int R, int S,
+                     int stride, int pad, int k_w, int k_a,
+                     const float *scale, const float *offset, int per_channel,
+                     int32_t *acc_out, float *out_f32, void *stream);
+
+/*
+ * Same call with the kernel variant chosen by the caller instead of the
+ * library's shape heuristic; exists so that measurements can sweep tilings.
+ * variant 0 = heuristic; ebs_conv_variant_count() gives the number of
+ * variants (valid values 0..count); a variant that cannot run the given shape
+ * returns EBS_ERR_UNSUPPORTED.  Results are identical for every variant.
+ */
+int ebs_conv_variant_count(void);
+const char *ebs_conv_variant_name(int variant);
+int ebs_mixed_conv2d_variant(int variant,
+                             const void *packed_act, const void *packed_wgt,
+                             int N, int C, int H, int W, int K, int R, int S,
+                             int stride, int pad, int k_w, int k_a,
+                             const float *scale, const float *offset, int per_channel,
+                             int32_t *acc_out, float *out_f32, void *stream);
+
+/*
+ * Measured comparison only (not the binary-decomposition path): the same
+ * integer convolution taken directly on the unpacked levels with int8 matrix
+ * instructions.  Same outputs and conventions as ebs_mixed_conv2d; needs
+ * C to be a multiple of 16 (EBS_ERR_UNSUPPORTED otherwise); levels must be
+ * below 128.
+ */
+int ebs_mixed_conv2d_mfma_i8(const uint8_t *act_levels_nhwc, const uint8_t *wgt_levels_krsc,
+                             int N, int C, int H, int W, int K, int R, int S,
+                             int stride, int pad,
+                             const float *scale, const float *offset, int per_channel,
+                             int32_t *acc_out, float *out_f32, void *stream);
+
+/*
+ * Debug aid: *device_flag (int32 on the device, cleared by this call) becomes
+ * non-zero if any of `count` levels is >= 2^bits.  The pack calls themselves
+ * never fail on range; they keep the low bits.
+ */
+int ebs_check_levels(const uint8_t *levels, size_t count, int bits,
+                     int32_t *device_flag, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EBS_H */

@@ -1,0 +1,164 @@
+"""ctypes binding with the same names as the C-ABI (include/ebs.h).
+
+Arguments are torch tensors (device memory) or raw integer device pointers;
+nothing is computed here.  If the shared library has not been built the first
+call raises: there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "libebs.so")
+_lib = None
+
+_vp = ctypes.c_void_p
+_ci = ctypes.c_int
+
+
+class EbsError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__(f"{what}: {ebs_status_string(status)} ({status})")
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Loads libebs.so; raises if it is missing (build it with build.py / __graft_entry__.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise FileNotFoundError(
+                f"{_LIB_PATH} is not built; run `python -m paper_2003_07577_amd.build` "
+                "(there is no non-HIP fallback)")
+        lib = ctypes.CDLL(_LIB_PATH)
+        lib.ebs_version.restype = _ci
+        lib.ebs_status_string.restype = ctypes.c_char_p
+        lib.ebs_status_string.argtypes = [_ci]
+        lib.ebs_packed_weights_bytes.restype = ctypes.c_size_t
+        lib.ebs_packed_weights_bytes.argtypes = [_ci] * 5
+        lib.ebs_packed_activations_bytes.restype = ctypes.c_size_t
+        lib.ebs_packed_activations_bytes.argtypes = [_ci] * 5
+        lib.ebs_pack_weights.restype = _ci
+        lib.ebs_pack_weights.argtypes = [_vp] + [_ci] * 5 + [_vp, _vp]
+        lib.ebs_pack_activations.restype = _ci
+        lib.ebs_pack_activations.argtypes = [_vp] + [_ci] * 5 + [_vp, _vp]
+        conv_tail = [_vp, _vp] + [_ci] * 11 + [_vp, _vp, _ci, _vp, _vp, _vp]
+        lib.ebs_mixed_conv2d.restype = _ci
+        lib.ebs_mixed_conv2d.argtypes = conv_tail
+        lib.ebs_mixed_conv2d_variant.restype = _ci
+        lib.ebs_mixed_conv2d_variant.argtypes = [_ci] + conv_tail
+        lib.ebs_conv_variant_count.restype = _ci
+        lib.ebs_conv_variant_name.restype = ctypes.c_char_p
+        lib.ebs_conv_variant_name.argtypes = [_ci]
+        lib.ebs_mixed_conv2d_mfma_i8.restype = _ci
+        lib.ebs_mixed_conv2d_mfma_i8.argtypes = [_vp, _vp] + [_ci] * 9 + [_vp, _vp, _ci, _vp, _vp, _vp]
+        lib.ebs_check_levels.restype = _ci
+        lib.ebs_check_levels.argtypes = [_vp, ctypes.c_size_t, _ci, _vp, _vp]
+        _lib = lib
+    return _lib
+
+
+def _ptr(x):
+    """Device pointer of a tensor-like (anything with data_ptr()), an int, or None."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    return x.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        return None
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream     # torch.cuda.Stream
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise EbsError(rc, what)
+
+
+def out_dims(H, W, R, S, stride, pad):
+    return (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
+
+
+def ebs_version() -> int:
+    return load_library().ebs_version()
+
+
+def ebs_status_string(status: int) -> str:
+    return load_library().ebs_status_string(status).decode()
+
+
+def ebs_packed_weights_bytes(K, C, R, S, k_w) -> int:
+    return load_library().ebs_packed_weights_bytes(K, C, R, S, k_w)
+
+
+def ebs_packed_activations_bytes(N, H, W, C, k_a) -> int:
+    return load_library().ebs_packed_activations_bytes(N, H, W, C, k_a)
+
+
+def ebs_pack_weights(levels_krsc, K, C, R, S, k_w, packed, stream=None, check=True) -> int:
+    rc = load_library().ebs_pack_weights(_ptr(levels_krsc), K, C, R, S, k_w, _ptr(packed), _stream(stream))
+    if check:
+        _check(rc, "ebs_pack_weights")
+    return rc
+
+
+def ebs_pack_activations(levels_nhwc, N, H, W, C, k_a, packed, stream=None, check=True) -> int:
+    rc = load_library().ebs_pack_activations(_ptr(levels_nhwc), N, H, W, C, k_a, _ptr(packed), _stream(stream))
+    if check:
+        _check(rc, "ebs_pack_activations")
+    return rc
+
+
+def ebs_mixed_conv2d(packed_act, packed_wgt, N, C, H, W, K, R, S, stride, pad, k_w, k_a,
+                     scale, offset, per_channel, acc_out, out_f32, stream=None, check=True) -> int:
+    rc = load_library().ebs_mixed_conv2d(
+        _ptr(packed_act), _ptr(packed_wgt), N, C, H, W, K, R, S, stride, pad, k_w, k_a,
+        _ptr(scale), _ptr(offset), int(bool(per_channel)), _ptr(acc_out), _ptr(out_f32), _stream(stream))
+    if check:
+        _check(rc, "ebs_mixed_conv2d")
+    return rc
+
+
+def ebs_conv_variant_count() -> int:
+    return load_library().ebs_conv_variant_count()
+
+
+def ebs_conv_variant_name(variant: int) -> str:
+    return load_library().ebs_conv_variant_name(variant).decode()
+
+
+def ebs_mixed_conv2d_variant(variant, packed_act, packed_wgt, N, C, H, W, K, R, S, stride, pad, k_w, k_a,
+                             scale, offset, per_channel, acc_out, out_f32, stream=None, check=True) -> int:
+    rc = load_library().ebs_mixed_conv2d_variant(
+        variant, _ptr(packed_act), _ptr(packed_wgt), N, C, H, W, K, R, S, stride, pad, k_w, k_a,
+        _ptr(scale), _ptr(offset), int(bool(per_channel)), _ptr(acc_out), _ptr(out_f32), _stream(stream))
+    if check:
+        _check(rc, "ebs_mixed_conv2d_variant")
+    return rc
+
+
+def ebs_mixed_conv2d_mfma_i8(act_levels_nhwc, wgt_levels_krsc, N, C, H, W, K, R, S, stride, pad,
+                             scale, offset, per_channel, acc_out, out_f32, stream=None, check=True) -> int:
+    rc = load_library().ebs_mixed_conv2d_mfma_i8(
+        _ptr(act_levels_nhwc), _ptr(wgt_levels_krsc), N, C, H, W, K, R, S, stride, pad,
+        _ptr(scale), _ptr(offset), int(bool(per_channel)), _ptr(acc_out), _ptr(out_f32), _stream(stream))
+    if check:
+        _check(rc, "ebs_mixed_conv2d_mfma_i8")
+    return rc
+
+
+def ebs_check_levels(levels, count, bits, device_flag, stream=None, check=True) -> int:
+    rc = load_library().ebs_check_levels(_ptr(levels), count, bits, _ptr(device_flag), _stream(stream))
+    if check:
+        _check(rc, "ebs_check_levels")
+    return rc

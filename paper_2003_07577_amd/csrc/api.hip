@@ -1,0 +1,183 @@
+// C-ABI entry points of libebs: argument validation and kernel dispatch.
+// Everything behind these calls runs in the library's own HIP kernels.
+#include "ebs_internal.h"
+
+namespace ebs {
+int pack_activations(const uint8_t *levels, uint32_t *packed, long long pixels, int C, int bits, hipStream_t st);
+int pack_weights(const uint8_t *levels, uint32_t *packed, int K, int C, int RS, int bits, hipStream_t st);
+int check_levels(const uint8_t *levels, size_t count, int bits, int32_t *flag, hipStream_t st);
+int launch_conv_mfma_i8(const uint8_t *act, const uint8_t *wgt, const ConvArgs &a);
+
+static const long long kMaxElems = (1LL << 31) - 1;
+
+static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+static bool bits_ok(int b) { return b >= 1 && b <= 4; }
+
+static int check_act_shape(int N, int H, int W, int C)
+{
+    if (N <= 0 || H <= 0 || W <= 0 || C <= 0) return EBS_ERR_SHAPE;
+    long long pixels = (long long)N * H * W;
+    if (pixels > kMaxElems || pixels * C > kMaxElems) return EBS_ERR_SHAPE;
+    if (pixels * words_per_pixel(C) * 4 > kMaxElems) return EBS_ERR_SHAPE;
+    return EBS_OK;
+}
+
+static int check_wgt_shape(int K, int C, int R, int S)
+{
+    if (K <= 0 || C <= 0 || R <= 0 || S <= 0) return EBS_ERR_SHAPE;
+    long long kpad = ((long long)K + kWgtGroup - 1) / kWgtGroup * kWgtGroup;
+    if ((long long)K * R * S * C > kMaxElems) return EBS_ERR_SHAPE;
+    if (kpad * R * S * words_per_pixel(C) * 4 > kMaxElems) return EBS_ERR_SHAPE;
+    return EBS_OK;
+}
+
+// Validates a convolution request and fills the geometry fields.
+static int check_conv(ConvArgs &a, const void *p0, const void *p1)
+{
+    if (!p0 || !p1 || !a.scale || !a.acc) return EBS_ERR_NULL;
+    if (!bits_ok(a.kw) || !bits_ok(a.ka)) return EBS_ERR_BITWIDTH;
+    int rc = check_act_shape(a.N, a.H, a.W, a.C);
+    if (rc) return rc;
+    rc = check_wgt_shape(a.K, a.C, a.R, a.S);
+    if (rc) return rc;
+    if (a.stride <= 0 || a.pad < 0 || a.pad >= a.R || a.pad >= a.S) return EBS_ERR_SHAPE;
+    if (a.H + 2 * a.pad < a.R || a.W + 2 * a.pad < a.S) return EBS_ERR_SHAPE;
+    a.OH = (a.H + 2 * a.pad - a.R) / a.stride + 1;
+    a.OW = (a.W + 2 * a.pad - a.S) / a.stride + 1;
+    a.cw = words_per_pixel(a.C);
+    if ((long long)a.N * a.OH * a.OW * a.K > kMaxElems) return EBS_ERR_SHAPE;
+    // the padded input plane is indexed with 32-bit integers inside the kernels
+    if ((long long)a.N * (a.H + 2 * a.pad) * (a.W + 2 * a.pad) > kMaxElems) return EBS_ERR_SHAPE;
+    if (!aligned16(p0) || !aligned16(p1) || !aligned16(a.acc) || (a.out && !aligned16(a.out))) return EBS_ERR_ALIGN;
+    if ((reinterpret_cast<uintptr_t>(a.scale) & 3u) || (a.offset && (reinterpret_cast<uintptr_t>(a.offset) & 3u)))
+        return EBS_ERR_ALIGN;
+    return EBS_OK;
+}
+
+static int run_conv(int variant, ConvArgs &a)
+{
+    int nt = conv_tiled_variant_count();
+    if (variant < 0 || variant > 1 + nt) return EBS_ERR_UNSUPPORTED;
+    if (variant == 1) return launch_conv_naive(a);
+    if (variant >= 2) return launch_conv_tiled(a, variant - 2);
+    int rc = launch_conv_tiled(a, -1);  // heuristic choice among the tiled variants
+    if (rc == EBS_ERR_UNSUPPORTED) rc = launch_conv_naive(a);
+    return rc;
+}
+
+}  // namespace ebs
+
+using namespace ebs;
+
+extern "C" {
+
+int ebs_version(void) { return 100; }
+
+const char *ebs_status_string(int s)
+{
+    switch (s) {
+        case EBS_OK: return "EBS_OK";
+        case EBS_ERR_NULL: return "EBS_ERR_NULL: required pointer is null";
+        case EBS_ERR_BITWIDTH: return "EBS_ERR_BITWIDTH: bitwidth outside [1,4]";
+        case EBS_ERR_SHAPE: return "EBS_ERR_SHAPE: invalid or too large shape";
+        case EBS_ERR_ALIGN: return "EBS_ERR_ALIGN: buffer not 16-byte aligned";
+        case EBS_ERR_UNSUPPORTED: return "EBS_ERR_UNSUPPORTED: no kernel for this request";
+        case EBS_ERR_HIP: return "EBS_ERR_HIP: HIP runtime error at launch";
+        case EBS_ERR_LEVEL_RANGE: return "EBS_ERR_LEVEL_RANGE: level exceeds bitwidth";
+    }
+    return "unknown ebs status";
+}
+
+size_t ebs_packed_weights_bytes(int K, int C, int R, int S, int k_w)
+{
+    if (!bits_ok(k_w) || check_wgt_shape(K, C, R, S)) return 0;
+    size_t kpad = ((size_t)K + kWgtGroup - 1) / kWgtGroup * kWgtGroup;
+    return kpad * R * S * words_per_pixel(C) * k_w * sizeof(uint32_t);
+}
+
+size_t ebs_packed_activations_bytes(int N, int H, int W, int C, int k_a)
+{
+    if (!bits_ok(k_a) || check_act_shape(N, H, W, C)) return 0;
+    return (size_t)N * H * W * words_per_pixel(C) * k_a * sizeof(uint32_t);
+}
+
+int ebs_pack_weights(const uint8_t *levels, int K, int C, int R, int S, int k_w, void *packed, void *stream)
+{
+    if (!levels || !packed) return EBS_ERR_NULL;
+    if (!bits_ok(k_w)) return EBS_ERR_BITWIDTH;
+    int rc = check_wgt_shape(K, C, R, S);
+    if (rc) return rc;
+    if (!aligned16(levels) || !aligned16(packed)) return EBS_ERR_ALIGN;
+    return pack_weights(levels, (uint32_t *)packed, K, C, R * S, k_w, (hipStream_t)stream);
+}
+
+int ebs_pack_activations(const uint8_t *levels, int N, int H, int W, int C, int k_a, void *packed, void *stream)
+{
+    if (!levels || !packed) return EBS_ERR_NULL;
+    if (!bits_ok(k_a)) return EBS_ERR_BITWIDTH;
+    int rc = check_act_shape(N, H, W, C);
+    if (rc) return rc;
+    if (!aligned16(levels) || !aligned16(packed)) return EBS_ERR_ALIGN;
+    return pack_activations(levels, (uint32_t *)packed, (long long)N * H * W, C, k_a, (hipStream_t)stream);
+}
+
+int ebs_conv_variant_count(void) { return 1 + conv_tiled_variant_count(); }
+
+const char *ebs_conv_variant_name(int v)
+{
+    if (v == 0) return "heuristic";
+    if (v == 1) return "naive";
+    if (v >= 2 && v < 2 + conv_tiled_variant_count()) return conv_tiled_variant_name(v - 2);
+    return "invalid";
+}
+
+int ebs_mixed_conv2d_variant(int variant, const void *packed_act, const void *packed_wgt,
+                             int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                             int k_w, int k_a, const float *scale, const float *offset, int per_channel,
+                             int32_t *acc_out, float *out_f32, void *stream)
+{
+    ConvArgs a{};
+    a.act = (const uint32_t *)packed_act;
+    a.wgt = (const uint32_t *)packed_wgt;
+    a.N = N; a.C = C; a.H = H; a.W = W; a.K = K; a.R = R; a.S = S;
+    a.stride = stride; a.pad = pad; a.kw = k_w; a.ka = k_a;
+    a.scale = scale; a.offset = offset; a.per_channel = per_channel ? 1 : 0;
+    a.acc = acc_out; a.out = out_f32; a.stream = (hipStream_t)stream;
+    int rc = check_conv(a, packed_act, packed_wgt);
+    if (rc) return rc;
+    return run_conv(variant, a);
+}
+
+int ebs_mixed_conv2d(const void *packed_act, const void *packed_wgt,
+                     int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                     int k_w, int k_a, const float *scale, const float *offset, int per_channel,
+                     int32_t *acc_out, float *out_f32, void *stream)
+{
+    return ebs_mixed_conv2d_variant(0, packed_act, packed_wgt, N, C, H, W, K, R, S, stride, pad, k_w, k_a,
+                                    scale, offset, per_channel, acc_out, out_f32, stream);
+}
+
+int ebs_mixed_conv2d_mfma_i8(const uint8_t *act_levels, const uint8_t *wgt_levels,
+                             int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                             const float *scale, const float *offset, int per_channel,
+                             int32_t *acc_out, float *out_f32, void *stream)
+{
+    ConvArgs a{};
+    a.N = N; a.C = C; a.H = H; a.W = W; a.K = K; a.R = R; a.S = S;
+    a.stride = stride; a.pad = pad; a.kw = 4; a.ka = 4;
+    a.scale = scale; a.offset = offset; a.per_channel = per_channel ? 1 : 0;
+    a.acc = acc_out; a.out = out_f32; a.stream = (hipStream_t)stream;
+    int rc = check_conv(a, act_levels, wgt_levels);
+    if (rc) return rc;
+    return launch_conv_mfma_i8(act_levels, wgt_levels, a);
+}
+
+int ebs_check_levels(const uint8_t *levels, size_t count, int bits, int32_t *device_flag, void *stream)
+{
+    if (!levels || !device_flag) return EBS_ERR_NULL;
+    if (bits < 1 || bits > 7) return EBS_ERR_BITWIDTH;
+    if (count == 0) return EBS_ERR_SHAPE;
+    return check_levels(levels, count, bits, device_flag, (hipStream_t)stream);
+}
+
+}  // extern "C"

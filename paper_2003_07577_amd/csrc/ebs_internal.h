@@ -1,0 +1,36 @@
+// Internal declarations shared by the translation units of libebs (host side).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "ebs.h"
+
+namespace ebs {
+
+// Weight words are grouped by 16 output channels so that one reduction step of
+// a channel tile is one contiguous run of words (see pack.hip).
+constexpr int kWgtGroup = 16;
+
+struct ConvArgs {
+    const uint32_t *act;   // packed activations  [N*H*W][cw][k_a]
+    const uint32_t *wgt;   // packed weights      [ceil(K/16)][R*S][cw][16][k_w]
+    int N, C, H, W, K, R, S, stride, pad, OH, OW, cw, kw, ka;
+    const float *scale;
+    const float *offset;   // may be null
+    int per_channel;
+    int32_t *acc;          // [N*OH*OW][K]
+    float *out;            // may be null
+    hipStream_t stream;
+};
+
+inline int words_per_pixel(int C) { return (C + 31) / 32; }
+
+int launch_conv_naive(const ConvArgs &a);
+// Returns EBS_ERR_UNSUPPORTED when the tiling cannot run this shape.
+int launch_conv_tiled(const ConvArgs &a, int variant);
+int conv_tiled_variant_count();
+const char *conv_tiled_variant_name(int variant);
+
+inline int hip_ok(hipError_t e) { return e == hipSuccess ? EBS_OK : EBS_ERR_HIP; }
+
+}  // namespace ebs

@@ -1,0 +1,102 @@
+"""Shared helpers for the GPU parity tests: run the hot path through the C-ABI
+on cuda:0 and bring results back as numpy.  Nothing here computes the method."""
+import numpy as np
+
+import paper_2003_07577_amd as ebs
+
+POISON = -842150451  # 0xCDCDCDCD as int32: an output the kernel forgot to write stands out
+
+
+def _dev():
+    import torch
+    assert torch.cuda.is_available(), "GPU test without a GPU"
+    return torch.device("cuda:0")
+
+
+def geometry(inp, stride, pad):
+    N, H, W, C = inp["a"].shape
+    K, R, S, _ = inp["q"].shape
+    OH, OW = ebs.out_dims(H, W, R, S, stride, pad)
+    return dict(N=N, C=C, H=H, W=W, K=K, R=R, S=S, stride=stride, pad=pad, OH=OH, OW=OW)
+
+
+def upload(inp, k_w, k_a, stride, pad):
+    """Device tensors for one case (levels, packed buffers, scale/offset, outputs)."""
+    import torch
+    dev = _dev()
+    g = geometry(inp, stride, pad)
+    d = dict(g=g, k_w=k_w, k_a=k_a)
+    d["a"] = torch.from_numpy(inp["a"]).to(dev)
+    d["q"] = torch.from_numpy(inp["q"]).to(dev)
+    nba = ebs.ebs_packed_activations_bytes(g["N"], g["H"], g["W"], g["C"], k_a)
+    nbw = ebs.ebs_packed_weights_bytes(g["K"], g["C"], g["R"], g["S"], k_w)
+    assert nba > 0 and nbw > 0
+    d["pa"] = torch.full((nba // 4,), POISON, dtype=torch.int32, device=dev)
+    d["pw"] = torch.full((nbw // 4,), POISON, dtype=torch.int32, device=dev)
+    d["scale"] = torch.from_numpy(np.ascontiguousarray(inp["scale"], dtype=np.float32)).to(dev)
+    d["offset"] = None if inp["offset"] is None else torch.from_numpy(
+        np.ascontiguousarray(inp["offset"], dtype=np.float32)).to(dev)
+    d["per_channel"] = bool(inp["per_channel"])
+    shape = (g["N"], g["OH"], g["OW"], g["K"])
+    d["acc"] = torch.full(shape, POISON, dtype=torch.int32, device=dev)
+    d["out"] = torch.full(shape, float("nan"), dtype=torch.float32, device=dev)
+    return d
+
+
+def pack(d, stream=None):
+    g = d["g"]
+    ebs.ebs_pack_weights(d["q"], g["K"], g["C"], g["R"], g["S"], d["k_w"], d["pw"], stream)
+    ebs.ebs_pack_activations(d["a"], g["N"], g["H"], g["W"], g["C"], d["k_a"], d["pa"], stream)
+
+
+def conv(d, variant=0, stream=None, want_f32=True):
+    g = d["g"]
+    ebs.ebs_mixed_conv2d_variant(variant, d["pa"], d["pw"], g["N"], g["C"], g["H"], g["W"], g["K"], g["R"], g["S"],
+                                 g["stride"], g["pad"], d["k_w"], d["k_a"], d["scale"], d["offset"],
+                                 d["per_channel"], d["acc"], d["out"] if want_f32 else None, stream)
+
+
+def run_case(inp, k_w, k_a, stride, pad, variant=0):
+    """Full hot path on the GPU; returns (acc int32 NHWC, out float32 NHWC, device dict)."""
+    import torch
+    d = upload(inp, k_w, k_a, stride, pad)
+    pack(d)
+    conv(d, variant)
+    torch.cuda.synchronize()
+    return d["acc"].cpu().numpy(), d["out"].cpu().numpy(), d
+
+
+def assert_f32_close(out, ref, acc_ref, scale, per_channel):
+    """|gpu - ref| <= 1e-5 * max(|ref|, |scale*acc|): 1e-5 relative, with the second
+    term guarding results that cancel against the offset."""
+    sc = np.asarray(scale, dtype=np.float64)
+    mag = np.abs(acc_ref.astype(np.float64) * (sc if per_channel else sc.reshape(-1)[0]))
+    tol = 1e-5 * np.maximum(np.abs(ref.astype(np.float64)), mag)
+    err = np.abs(out.astype(np.float64) - ref.astype(np.float64))
+    bad = err > tol
+    assert not bad.any(), f"{int(bad.sum())} fp32 outputs beyond 1e-5 relative; worst {err.max()}"
+
+
+def unpack_activations(words, N, H, W, C, k_a):
+    """Test-side inverse of the activation packing: uint32 [pixel][word][plane] -> levels."""
+    cw = (C + 31) // 32
+    w = np.asarray(words).view(np.uint32).reshape(N * H * W, cw, k_a)
+    bits = ((w[:, :, :, None] >> np.arange(32, dtype=np.uint32)) & 1).astype(np.uint8)  # pix, word, plane, bit
+    lv = np.zeros((N * H * W, cw, 32), np.uint8)
+    for j in range(k_a):
+        lv |= bits[:, :, j, :] << j
+    full = lv.reshape(N * H * W, cw * 32)
+    return full[:, :C].reshape(N, H, W, C), full[:, C:]
+
+
+def unpack_weights(words, K, C, R, S, k_w):
+    """uint32 [k/16][tap][word][k%16][plane] -> levels KRSC (and the padded remainder)."""
+    cw = (C + 31) // 32
+    kg = (K + 15) // 16
+    w = np.asarray(words).view(np.uint32).reshape(kg, R * S, cw, 16, k_w)
+    bits = ((w[..., None] >> np.arange(32, dtype=np.uint32)) & 1).astype(np.uint8)  # kg,tap,word,kl,plane,bit
+    lv = np.zeros((kg, R * S, cw, 16, 32), np.uint8)
+    for i in range(k_w):
+        lv |= bits[:, :, :, :, i, :] << i
+    lv = lv.transpose(0, 3, 1, 2, 4).reshape(kg * 16, R * S, cw * 32)
+    return lv[:K, :, :C].reshape(K, R, S, C), lv[K:], lv[:K, :, C:]

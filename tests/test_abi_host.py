@@ -1,0 +1,119 @@
+"""Host-only checks of the C-ABI: the library loads, exports every symbol the
+header declares, and rejects bad arguments before anything is enqueued (no GPU
+is touched: every call below fails validation on the host)."""
+import os
+import re
+
+import pytest
+
+import paper_2003_07577_amd as ebs
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x10000  # a non-null, 16-byte aligned value; never dereferenced by the host
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(ebs.library_path()):
+        from paper_2003_07577_amd.build import build_library
+        build_library()
+    return ebs.load_library()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = set()
+    for fn in os.listdir(os.path.join(ROOT, "include")):
+        if fn.endswith(".h"):
+            text = open(os.path.join(ROOT, "include", fn)).read()
+            text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+            names |= set(re.findall(r"\b(ebs_[a-z0-9_]+)\s*\(", text))
+    assert {"ebs_pack_weights", "ebs_pack_activations", "ebs_mixed_conv2d"} <= names
+    for n in sorted(names):
+        assert hasattr(lib, n), f"{n} declared in include/ but not exported"
+
+
+def test_version_and_status_strings(lib):
+    assert ebs.ebs_version() >= 100
+    assert ebs.ebs_status_string(0) == "EBS_OK"
+    for s in range(-7, 0):
+        assert ebs.ebs_status_string(s).startswith("EBS_ERR_")
+    assert "unknown" in ebs.ebs_status_string(-99)
+
+
+def test_packed_sizes(lib):
+    # activations: N*H*W pixels x ceil(C/32) words x k_a planes x 4 bytes
+    assert ebs.ebs_packed_activations_bytes(64, 56, 56, 64, 4) == 64 * 56 * 56 * 2 * 4 * 4
+    assert ebs.ebs_packed_activations_bytes(1, 8, 8, 16, 2) == 64 * 1 * 2 * 4
+    assert ebs.ebs_packed_activations_bytes(1, 1, 1, 33, 1) == 2 * 4
+    # weights: K rounded up to 16
+    assert ebs.ebs_packed_weights_bytes(64, 64, 3, 3, 1) == 64 * 9 * 2 * 4
+    assert ebs.ebs_packed_weights_bytes(1000, 2048, 1, 1, 4) == 1008 * 64 * 4 * 4
+    for bad in [(0, 8, 8, 16, 2), (1, 8, 8, 16, 0), (1, 8, 8, 16, 5), (1, -1, 8, 16, 2)]:
+        assert ebs.ebs_packed_activations_bytes(*bad) == 0
+    assert ebs.ebs_packed_weights_bytes(16, 16, 3, 3, 9) == 0
+    assert ebs.ebs_packed_weights_bytes(16, 0, 3, 3, 2) == 0
+
+
+def _conv(**kw):
+    d = dict(packed_act=FAKE, packed_wgt=FAKE, N=1, C=16, H=8, W=8, K=16, R=3, S=3, stride=1, pad=1,
+             k_w=2, k_a=2, scale=FAKE, offset=None, per_channel=0, acc_out=FAKE, out_f32=FAKE)
+    d.update(kw)
+    return ebs.ebs_mixed_conv2d(d["packed_act"], d["packed_wgt"], d["N"], d["C"], d["H"], d["W"], d["K"],
+                                d["R"], d["S"], d["stride"], d["pad"], d["k_w"], d["k_a"], d["scale"],
+                                d["offset"], d["per_channel"], d["acc_out"], d["out_f32"], None, check=False)
+
+
+def test_conv_argument_errors(lib):
+    E = {n: v for n, v in [("NULL", -1), ("BITS", -2), ("SHAPE", -3), ("ALIGN", -4)]}
+    assert _conv(packed_act=None) == E["NULL"]
+    assert _conv(packed_wgt=None) == E["NULL"]
+    assert _conv(scale=None) == E["NULL"]
+    assert _conv(acc_out=None) == E["NULL"]
+    for k in (0, 5, -1):
+        assert _conv(k_w=k) == E["BITS"]
+        assert _conv(k_a=k) == E["BITS"]
+    for bad in [dict(N=0), dict(C=0), dict(H=-2), dict(W=0), dict(K=0), dict(R=0), dict(S=0),
+                dict(stride=0), dict(pad=-1), dict(pad=3), dict(H=1, W=1, pad=0),
+                dict(N=1 << 20, H=1 << 10, W=1 << 10)]:
+        assert _conv(**bad) == E["SHAPE"], bad
+    assert _conv(packed_act=FAKE + 4) == E["ALIGN"]
+    assert _conv(acc_out=FAKE + 8) == E["ALIGN"]
+    assert _conv(out_f32=FAKE + 2) == E["ALIGN"]
+    assert _conv(scale=FAKE + 1) == E["ALIGN"]
+    with pytest.raises(ebs.EbsError) as ei:
+        ebs.ebs_mixed_conv2d(None, FAKE, 1, 16, 8, 8, 16, 3, 3, 1, 1, 2, 2, FAKE, None, 0, FAKE, FAKE)
+    assert ei.value.status == -1
+
+
+def test_pack_argument_errors(lib):
+    assert ebs.ebs_pack_weights(None, 16, 16, 3, 3, 2, FAKE, check=False) == -1
+    assert ebs.ebs_pack_weights(FAKE, 16, 16, 3, 3, 2, None, check=False) == -1
+    assert ebs.ebs_pack_weights(FAKE, 16, 16, 3, 3, 7, FAKE, check=False) == -2
+    assert ebs.ebs_pack_weights(FAKE, 0, 16, 3, 3, 2, FAKE, check=False) == -3
+    assert ebs.ebs_pack_weights(FAKE, 16, 16, 3, 3, 2, FAKE + 4, check=False) == -4
+    assert ebs.ebs_pack_activations(None, 1, 8, 8, 16, 2, FAKE, check=False) == -1
+    assert ebs.ebs_pack_activations(FAKE, 1, 8, 8, 16, 0, FAKE, check=False) == -2
+    assert ebs.ebs_pack_activations(FAKE, 1, 8, 0, 16, 2, FAKE, check=False) == -3
+    assert ebs.ebs_pack_activations(FAKE + 1, 1, 8, 8, 16, 2, FAKE, check=False) == -4
+    assert ebs.ebs_check_levels(None, 10, 2, FAKE, check=False) == -1
+    assert ebs.ebs_check_levels(FAKE, 0, 2, FAKE, check=False) == -3
+    assert ebs.ebs_check_levels(FAKE, 10, 0, FAKE, check=False) == -2
+
+
+def test_variant_errors(lib):
+    n = ebs.ebs_conv_variant_count()
+    assert n >= 1
+    assert ebs.ebs_conv_variant_name(0) == "heuristic"
+    assert ebs.ebs_conv_variant_name(1) == "naive"
+    rc = ebs.ebs_mixed_conv2d_variant(n + 5, FAKE, FAKE, 1, 16, 8, 8, 16, 3, 3, 1, 1, 2, 2, FAKE, None, 0,
+                                      FAKE, FAKE, None, check=False)
+    assert rc == -5
+
+
+def test_mfma_argument_errors(lib):
+    rc = ebs.ebs_mixed_conv2d_mfma_i8(None, FAKE, 1, 16, 8, 8, 16, 3, 3, 1, 1, FAKE, None, 0, FAKE, FAKE, None,
+                                      check=False)
+    assert rc == -1
+    rc = ebs.ebs_mixed_conv2d_mfma_i8(FAKE, FAKE, 1, 16, 8, 8, 16, 3, 3, 1, 5, FAKE, None, 0, FAKE, FAKE, None,
+                                      check=False)
+    assert rc == -3
