@@ -1,0 +1,269 @@
+#!/usr/bin/env python3
+"""Benchmark of the binary-decomposition mixed-precision convolution on one MI355X.
+
+One "step" is one pass of the whole hot path over one batch of synthetic input:
+for every case of the workload (a layer shape at one (k_w, k_a) pair) the
+activation bit-plane packing followed by the AND+popcount convolution with its
+fused shift-accumulate and scale/offset epilogue.  Weight packing is done once
+before timing (it is an offline step in the paper's deployment flow, Sec. 4.3).
+All inputs are resident in HBM before the timed region starts.
+
+Prints ONE JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# Integer-ALU roofline of the AND+popcount inner product on MI355X: 256 CUs x 64
+# int32 lanes per clock x 2.4 GHz = 39.3 T lane-ops/s; 32 binary MACs cost two
+# lane-ops (v_and_b32 + accumulating v_bcnt_u32_b32) and count as 64 binary ops.
+ALU_LANE_OPS = 256 * 64 * 2.4e9
+PEAK_BINARY_TOPS = ALU_LANE_OPS / 2 * 64 / 1e12      # 1258.3
+HBM_PEAK_GBS = 8000.0
+
+WORKLOADS = {"tiny": 1, "cifar20": 2, "resnet18": 3, "resnet50": 4, "fc": 5}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="resnet18", choices=sorted(WORKLOADS))
+    ap.add_argument("--kernel-reps", type=int, default=10, help="back-to-back launches per case for per-kernel timing")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cases-out", default=None, help="write the per-case table (JSON) here")
+    ap.add_argument("--variant", type=int, default=0, help="conv kernel variant (0 = library heuristic)")
+    return ap.parse_args()
+
+
+class CaseBuffers:
+    """Device-resident tensors of one case (torch owns memory only)."""
+
+    def __init__(self, case, inputs, shared, dev):
+        import torch
+        import paper_2003_07577_amd as ebs
+        L = case.layer
+        self.case = case
+        self.a = torch.from_numpy(inputs["a"]).to(dev)
+        q = torch.from_numpy(inputs["q"]).to(dev)
+        self.pa = torch.empty(ebs.ebs_packed_activations_bytes(L.N, L.H, L.W, L.C, case.k_a) // 4,
+                              dtype=torch.int32, device=dev)
+        self.pw = torch.empty(ebs.ebs_packed_weights_bytes(L.K, L.C, L.R, L.S, case.k_w) // 4,
+                              dtype=torch.int32, device=dev)
+        ebs.ebs_pack_weights(q, L.K, L.C, L.R, L.S, case.k_w, self.pw)          # offline step
+        self.scale = torch.from_numpy(inputs["scale"]).to(dev)
+        self.offset = None if inputs["offset"] is None else torch.from_numpy(inputs["offset"]).to(dev)
+        self.per_channel = inputs["per_channel"]
+        n_out = L.N * L.OH * L.OW * L.K
+        # output buffers are rotated among a few allocations so that consecutive
+        # cases do not rewrite lines that are still in the last-level cache
+        self.acc, self.out = shared.outputs(n_out)
+
+    def pack(self, ebs, stream):
+        L = self.case.layer
+        ebs.ebs_pack_activations(self.a, L.N, L.H, L.W, L.C, self.case.k_a, self.pa, stream)
+
+    def conv(self, ebs, stream, variant=0):
+        L, c = self.case.layer, self.case
+        ebs.ebs_mixed_conv2d_variant(variant, self.pa, self.pw, L.N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad,
+                                     c.k_w, c.k_a, self.scale, self.offset, self.per_channel, self.acc, self.out,
+                                     stream)
+
+
+class SharedOutputs:
+    def __init__(self, dev, max_elems, n_slots=4):
+        import torch
+        self.slots = [(torch.empty(max_elems, dtype=torch.int32, device=dev),
+                       torch.empty(max_elems, dtype=torch.float32, device=dev)) for _ in range(n_slots)]
+        self.i = 0
+
+    def outputs(self, n):
+        acc, out = self.slots[self.i % len(self.slots)]
+        self.i += 1
+        return acc[:n], out[:n]
+
+
+def conv_bytes(case):
+    """Algorithmic HBM bytes of one convolution launch: packed operands once, int32+fp32 outputs once."""
+    L = case.layer
+    cw = (L.C + 31) // 32
+    return (L.N * L.H * L.W * cw * case.k_a * 4 + ((L.K + 15) // 16 * 16) * L.R * L.S * cw * case.k_w * 4
+            + L.N * L.OH * L.OW * L.K * 8)
+
+
+def pack_bytes(case):
+    L = case.layer
+    cw = (L.C + 31) // 32
+    return L.N * L.H * L.W * (L.C + cw * case.k_a * 4)
+
+
+def cpu_baseline(cases):
+    """The oracle as it stands, timed on the host cores: each distinct layer shape once
+    (its time does not depend on the bitwidths), aggregated over the cases of the workload."""
+    import numpy as np
+    import oracle
+    import ebs_workloads as wl
+    oracle.build()
+    per_layer = {}
+    layers = []
+    for c in cases:
+        if c.layer not in per_layer:
+            per_layer[c.layer] = []
+            layers.append((c.layer, wl.make_inputs(c)))
+    t_begin = time.time()
+    passes = 0
+    while passes == 0 or (time.time() - t_begin < 12.0 and passes < 50):   # about 10-20 s of CPU work
+        for L, inp in layers:
+            t0 = time.time()
+            oracle.conv2d_levels(inp["a"], inp["q"], L.stride, L.pad)
+            per_layer[L].append(time.time() - t0)
+        passes += 1
+        print(f"[cpu_baseline] pass {passes} done at {time.time() - t_begin:.1f}s", file=sys.stderr, flush=True)
+    total_cpu_s = sum(sum(v) for v in per_layer.values())
+    per_layer = {L: sum(v) / len(v) for L, v in per_layer.items()}
+    covered = [c for c in cases if c.layer in per_layer]
+    ops = sum(c.binary_ops for c in covered)
+    secs = sum(per_layer[c.layer] for c in covered)
+    macs = sum(L.int_macs for L in per_layer)
+    return {
+        "value": ops / secs / 1e12, "unit": "TOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+        "sample": (f"direct integer conv, each of {len(per_layer)} layer shapes of the workload at full batch "
+                   f"per pass ({macs / 1e9:.1f} G int-MACs), {passes} passes, {total_cpu_s:.1f}s in all; time is bitwidth-independent, "
+                   f"so the rate is aggregated over the {len(covered)} (layer, k_w, k_a) cases like the GPU value"),
+        "int_gmacs_per_s": macs / sum(per_layer.values()) / 1e9,
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
+              f"--gpus {args.gpus} is not supported. Re-run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import ebs_workloads as wl
+    import paper_2003_07577_amd as ebs
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(1)
+    ebs.load_library()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    stream = torch.cuda.current_stream()
+
+    cfg = WORKLOADS[args.workload]
+    cases = wl.config_cases(cfg)
+    max_out = max(c.layer.N * c.layer.OH * c.layer.OW * c.layer.K for c in cases)
+    shared = SharedOutputs(dev, max_out)
+    bufs = []
+    for c in cases:
+        bufs.append(CaseBuffers(c, wl.make_inputs(c), shared, dev))
+    torch.cuda.synchronize()
+
+    def step():
+        for b in bufs:
+            b.pack(ebs, stream)
+            b.conv(ebs, stream, args.variant)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.time()
+    e0.record(stream)
+    for _ in range(args.steps):
+        step()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    wall = time.time() - t0
+    ms_total = e0.elapsed_time(e1)
+    ms_per_step = ms_total / args.steps
+    ops_per_step = sum(c.binary_ops for c in cases)
+    value = ops_per_step / (ms_per_step * 1e-3) / 1e12
+
+    # ---- per-kernel timing, live, with events on the launch stream
+    table = []
+    conv_us_sum = pack_us_sum = 0.0
+    conv_ops = 0
+    conv_bytes_sum = pack_bytes_sum = 0
+    for b in bufs:
+        c = b.case
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        b.pack(ebs, stream)
+        b.conv(ebs, stream, args.variant)
+        ev[0].record(stream)
+        for _ in range(args.kernel_reps):
+            b.pack(ebs, stream)
+        ev[1].record(stream)
+        for _ in range(args.kernel_reps):
+            b.conv(ebs, stream, args.variant)
+        ev[2].record(stream)
+        torch.cuda.synchronize()
+        pack_us = ev[0].elapsed_time(ev[1]) * 1e3 / args.kernel_reps
+        conv_us = ev[1].elapsed_time(ev[2]) * 1e3 / args.kernel_reps
+        conv_us_sum += conv_us
+        pack_us_sum += pack_us
+        conv_ops += c.binary_ops
+        conv_bytes_sum += conv_bytes(c)
+        pack_bytes_sum += pack_bytes(c)
+        tops = c.binary_ops / conv_us / 1e6
+        t_alu = c.binary_ops / PEAK_BINARY_TOPS / 1e6
+        t_hbm = conv_bytes(c) / HBM_PEAK_GBS / 1e3
+        table.append({
+            "case": c.tag, "layer": c.layer.name, "k_w": c.k_w, "k_a": c.k_a,
+            "conv_us": round(conv_us, 2), "pack_us": round(pack_us, 2),
+            "binary_tops": round(tops, 1), "alu_frac": round(tops / PEAK_BINARY_TOPS, 4),
+            "conv_hbm_gbs": round(conv_bytes(c) / conv_us / 1e3, 1),
+            "pack_hbm_gbs": round(pack_bytes(c) / pack_us / 1e3, 1),
+            "binding_roof": "alu" if t_alu >= t_hbm else "hbm",
+            "roof_us": round(max(t_alu, t_hbm), 2),
+        })
+    achieved = conv_ops / conv_us_sum / 1e6
+    roofline = {
+        "kernel": "bd_conv (AND+popcount convolution, all launches of the workload)",
+        "bound": "alu", "achieved": round(achieved, 2), "peak": round(PEAK_BINARY_TOPS, 1), "unit": "TOP/s",
+        "frac": round(achieved / PEAK_BINARY_TOPS, 4), "traffic": None,
+        "avg_launch_us": round(conv_us_sum / len(bufs), 2),
+        "hbm_gbs_algorithmic": round(conv_bytes_sum / conv_us_sum / 1e3, 1),
+        "min_case_frac": min(r["alu_frac"] for r in table), "max_case_frac": max(r["alu_frac"] for r in table),
+    }
+    pack_roof = {
+        "kernel": "pack_activations", "bound": "hbm", "achieved": round(pack_bytes_sum / pack_us_sum / 1e3, 1),
+        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(pack_bytes_sum / pack_us_sum / 1e3 / HBM_PEAK_GBS, 4),
+        "avg_launch_us": round(pack_us_sum / len(bufs), 2),
+    }
+
+    out = {
+        "metric": "effective binary TOP/s of mixed-precision conv layers (pack_activations + conv per layer)",
+        "value": round(value, 2), "unit": "TOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u32 bit-planes, int32 accumulate, fp32 epilogue", "data": "synthetic",
+        "config": {"workload": f"configs[{cfg - 1}] {args.workload}: {len(cases)} (layer, k_w, k_a) cases, "
+                               f"N={cases[0].layer.N}", "cases": len(cases), "variant": args.variant},
+        "conv_only_tops": round(achieved, 2),
+        "wall_s": round(wall, 3),
+        "roofline": roofline, "pack_roofline": pack_roof,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cases)
+    cases_out = args.cases_out
+    if cases_out is None and os.path.isdir(os.path.join(ROOT, "gpurun_out")):
+        cases_out = os.path.join(ROOT, "gpurun_out", f"bench_cases_{args.workload}.json")
+    if cases_out:
+        with open(cases_out, "w") as f:
+            json.dump(table, f, indent=1)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
