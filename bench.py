@@ -96,14 +96,14 @@ def conv_bytes(case):
     """Algorithmic HBM bytes of one convolution launch: packed operands once, int32+fp32 outputs once."""
     L = case.layer
     cw = (L.C + 31) // 32
-    return (L.N * L.H * L.W * cw * case.k_a * 4 + ((L.K + 15) // 16 * 16) * L.R * L.S * cw * case.k_w * 4
+    return (L.N * (L.H + 2) * (L.W + 2) * cw * case.k_a * 4 + ((L.K + 15) // 16 * 16) * L.R * L.S * cw * case.k_w * 4
             + L.N * L.OH * L.OW * L.K * 8)
 
 
 def pack_bytes(case):
     L = case.layer
     cw = (L.C + 31) // 32
-    return L.N * L.H * L.W * (L.C + cw * case.k_a * 4)
+    return L.N * L.H * L.W * L.C + L.N * (L.H + 2) * (L.W + 2) * cw * case.k_a * 4
 
 
 def cpu_baseline(cases):

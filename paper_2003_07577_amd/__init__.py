@@ -14,6 +14,9 @@ from .binding import (  # noqa: F401
     ebs_mixed_conv2d_variant,
     ebs_pack_activations,
     ebs_pack_weights,
+    ebs_probe_and_bcnt,
+    ebs_probe_and_bcnt_pairs,
+    ebs_probe_copy,
     ebs_packed_activations_bytes,
     ebs_packed_weights_bytes,
     ebs_status_string,

@@ -59,6 +59,12 @@ def load_library():
         lib.ebs_mixed_conv2d_mfma_i8.argtypes = [_vp, _vp] + [_ci] * 9 + [_vp, _vp, _ci, _vp, _vp, _vp]
         lib.ebs_check_levels.restype = _ci
         lib.ebs_check_levels.argtypes = [_vp, ctypes.c_size_t, _ci, _vp, _vp]
+        lib.ebs_probe_and_bcnt.restype = _ci
+        lib.ebs_probe_and_bcnt.argtypes = [_vp, _vp, _ci, _ci, _vp]
+        lib.ebs_probe_and_bcnt_pairs.restype = ctypes.c_longlong
+        lib.ebs_probe_and_bcnt_pairs.argtypes = [_ci, _ci]
+        lib.ebs_probe_copy.restype = _ci
+        lib.ebs_probe_copy.argtypes = [_vp, _vp, ctypes.c_size_t, _ci, _vp]
         _lib = lib
     return _lib
 
@@ -161,4 +167,22 @@ def ebs_check_levels(levels, count, bits, device_flag, stream=None, check=True) 
     rc = load_library().ebs_check_levels(_ptr(levels), count, bits, _ptr(device_flag), _stream(stream))
     if check:
         _check(rc, "ebs_check_levels")
+    return rc
+
+
+def ebs_probe_and_bcnt(seed, sink, blocks, trips, stream=None, check=True) -> int:
+    rc = load_library().ebs_probe_and_bcnt(_ptr(seed), _ptr(sink), blocks, trips, _stream(stream))
+    if check:
+        _check(rc, "ebs_probe_and_bcnt")
+    return rc
+
+
+def ebs_probe_and_bcnt_pairs(blocks, trips) -> int:
+    return load_library().ebs_probe_and_bcnt_pairs(blocks, trips)
+
+
+def ebs_probe_copy(src, dst, nbytes, blocks, stream=None, check=True) -> int:
+    rc = load_library().ebs_probe_copy(_ptr(src), _ptr(dst), nbytes, blocks, _stream(stream))
+    if check:
+        _check(rc, "ebs_probe_copy")
     return rc

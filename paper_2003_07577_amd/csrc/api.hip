@@ -3,7 +3,7 @@
 #include "ebs_internal.h"
 
 namespace ebs {
-int pack_activations(const uint8_t *levels, uint32_t *packed, long long pixels, int C, int bits, hipStream_t st);
+int pack_activations(const uint8_t *levels, uint32_t *packed, int N, int H, int W, int C, int bits, hipStream_t st);
 int pack_weights(const uint8_t *levels, uint32_t *packed, int K, int C, int RS, int bits, hipStream_t st);
 int check_levels(const uint8_t *levels, size_t count, int bits, int32_t *flag, hipStream_t st);
 int launch_conv_mfma_i8(const uint8_t *act, const uint8_t *wgt, const ConvArgs &a);
@@ -18,7 +18,8 @@ static int check_act_shape(int N, int H, int W, int C)
     if (N <= 0 || H <= 0 || W <= 0 || C <= 0) return EBS_ERR_SHAPE;
     long long pixels = (long long)N * H * W;
     if (pixels > kMaxElems || pixels * C > kMaxElems) return EBS_ERR_SHAPE;
-    if (pixels * words_per_pixel(C) * 4 > kMaxElems) return EBS_ERR_SHAPE;
+    long long padded = (long long)N * (H + 2 * kActBorder) * (W + 2 * kActBorder);
+    if (padded * words_per_pixel(C) * 4 + kActTailDwords > kMaxElems) return EBS_ERR_SHAPE;
     return EBS_OK;
 }
 
@@ -46,8 +47,6 @@ static int check_conv(ConvArgs &a, const void *p0, const void *p1)
     a.OW = (a.W + 2 * a.pad - a.S) / a.stride + 1;
     a.cw = words_per_pixel(a.C);
     if ((long long)a.N * a.OH * a.OW * a.K > kMaxElems) return EBS_ERR_SHAPE;
-    // the padded input plane is indexed with 32-bit integers inside the kernels
-    if ((long long)a.N * (a.H + 2 * a.pad) * (a.W + 2 * a.pad) > kMaxElems) return EBS_ERR_SHAPE;
     if (!aligned16(p0) || !aligned16(p1) || !aligned16(a.acc) || (a.out && !aligned16(a.out))) return EBS_ERR_ALIGN;
     if ((reinterpret_cast<uintptr_t>(a.scale) & 3u) || (a.offset && (reinterpret_cast<uintptr_t>(a.offset) & 3u)))
         return EBS_ERR_ALIGN;
@@ -98,7 +97,8 @@ size_t ebs_packed_weights_bytes(int K, int C, int R, int S, int k_w)
 size_t ebs_packed_activations_bytes(int N, int H, int W, int C, int k_a)
 {
     if (!bits_ok(k_a) || check_act_shape(N, H, W, C)) return 0;
-    return (size_t)N * H * W * words_per_pixel(C) * k_a * sizeof(uint32_t);
+    size_t padded = (size_t)N * (H + 2 * kActBorder) * (W + 2 * kActBorder);
+    return (padded * words_per_pixel(C) * k_a + kActTailDwords) * sizeof(uint32_t);
 }
 
 int ebs_pack_weights(const uint8_t *levels, int K, int C, int R, int S, int k_w, void *packed, void *stream)
@@ -118,7 +118,7 @@ int ebs_pack_activations(const uint8_t *levels, int N, int H, int W, int C, int 
     int rc = check_act_shape(N, H, W, C);
     if (rc) return rc;
     if (!aligned16(levels) || !aligned16(packed)) return EBS_ERR_ALIGN;
-    return pack_activations(levels, (uint32_t *)packed, (long long)N * H * W, C, k_a, (hipStream_t)stream);
+    return pack_activations(levels, (uint32_t *)packed, N, H, W, C, k_a, (hipStream_t)stream);
 }
 
 int ebs_conv_variant_count(void) { return 1 + conv_tiled_variant_count(); }

@@ -28,13 +28,14 @@ bd_conv_naive(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
     for (int c = 0; c < NCLS; ++c) cls[c] = 0u;
     const int RS = R * S;
     const uint32_t *wk = wgt + ((long long)(k / kWgtGroup) * RS * cw * kWgtGroup + (k % kWgtGroup)) * KW;
+    const int Hp = H + 2 * kActBorder, Wp = W + 2 * kActBorder;
     for (int r = 0; r < R; ++r) {
-        int h = oh * stride + r - pad;
-        if (h < 0 || h >= H) continue;
+        int hp = oh * stride + r - pad + kActBorder;      // row in the bordered grid
+        if (hp < 0 || hp >= Hp) continue;                // beyond the stored zero ring: contributes 0
         for (int s = 0; s < S; ++s) {
-            int w = ow * stride + s - pad;
-            if (w < 0 || w >= W) continue;
-            const uint32_t *ap = act + (((n * H + h) * W + w) * cw) * KA;
+            int wcol = ow * stride + s - pad + kActBorder;
+            if (wcol < 0 || wcol >= Wp) continue;
+            const uint32_t *ap = act + (((n * Hp + hp) * Wp + wcol) * cw) * KA;
             const uint32_t *wp = wk + (long long)(r * S + s) * cw * kWgtGroup * KW;
             for (int word = 0; word < cw; ++word) {
                 uint32_t x[KA], q[KW];

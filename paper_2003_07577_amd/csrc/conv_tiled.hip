@@ -11,10 +11,13 @@ template <> int launch_tiled_kw<3>(const ConvArgs &a, int v);
 template <> int launch_tiled_kw<4>(const ConvArgs &a, int v);
 
 static const char *const kNames[] = {
-    "tile128.ch2", "tile128.ch1", "tile128.ch4",
-    "tile64.ch2", "tile64.ch1", "tile64.ch4",
-    "tile32.ch2", "tile32.ch1", "tile32.ch4",
-    "split4.tile64.ch4", "split4.tile32.ch4",
+    "p4.tile128.ch2", "p4.tile128.ch1", "p4.tile128.ch4",
+    "p4.tile64.ch2", "p4.tile64.ch1", "p4.tile64.ch4",
+    "p4.tile32.ch2", "p4.tile32.ch1", "p4.tile32.ch4",
+    "k4.tile128.ch2", "k4.tile128.ch1", "k4.tile128.ch4",
+    "k4.tile64.ch2", "k4.tile64.ch1", "k4.tile64.ch4",
+    "k4.tile32.ch2", "k4.tile32.ch1", "k4.tile32.ch4",
+    "r4.tile128.ch4", "r4.tile64.ch4", "r4.tile32.ch4",
 };
 static constexpr int kNumVariants = sizeof(kNames) / sizeof(kNames[0]);
 
@@ -44,7 +47,7 @@ int launch_conv_tiled(const ConvArgs &a, int variant)
     long long outputs = (long long)a.N * a.OH * a.OW * a.K;
     int order[5];
     int n = 0;
-    if (outputs < (1 << 22) && a.cw >= 4) order[n++] = 9;
+    if (outputs < (1 << 22) && a.cw >= 4) order[n++] = 19;
     order[n++] = 3 + ch_index(a.cw);
     order[n++] = 6 + ch_index(a.cw);
     order[n++] = 7;

@@ -12,7 +12,7 @@ namespace ebs {
 constexpr int kWgtGroup = 16;
 
 struct ConvArgs {
-    const uint32_t *act;   // packed activations  [N*H*W][cw][k_a]
+    const uint32_t *act;   // packed activations  [N][H+2][W+2][cw][k_a], zero border of one position
     const uint32_t *wgt;   // packed weights      [ceil(K/16)][R*S][cw][16][k_w]
     int N, C, H, W, K, R, S, stride, pad, OH, OW, cw, kw, ka;
     const float *scale;
@@ -24,6 +24,14 @@ struct ConvArgs {
 };
 
 inline int words_per_pixel(int C) { return (C + 31) / 32; }
+
+// Packed activations carry a zero border of this many positions on every side
+// of each image, so that a 3x3 / pad-1 filter tap never leaves the buffer and
+// needs no bounds check.
+constexpr int kActBorder = 1;
+// Slack dwords after the last position so that vector loads of a few words may
+// run past the end of the last position.
+constexpr int kActTailDwords = 4;
 
 int launch_conv_naive(const ConvArgs &a);
 // Returns EBS_ERR_UNSUPPORTED when the tiling cannot run this shape.

@@ -1,26 +1,28 @@
 // Host-side geometry of the tiled convolution (plain C++, no HIP): how many
 // padded input positions a tile of consecutive output positions can touch.
 //
-// Output positions are numbered t = (n*OH + oh)*OW + ow.  The zero-padded
-// input of all images is viewed as one flat array of positions
-// u = (n*Hp + hp)*Wp + wp with Hp = H + 2*pad, Wp = W + 2*pad.  Output t reads,
+// Output positions are numbered t = (n*OH + oh)*OW + ow.  The packed
+// activations are stored with a zero border of `border` positions around every
+// image, i.e. as one flat array of positions u = (n*Hp + hp)*Wp + wp with
+// Hp = H + 2*border, Wp = W + 2*border.  With pad <= border, output t reads,
 // for filter tap (r, s), position base(t) + r*Wp + s where
-// base(t) = (n*Hp + oh*stride)*Wp + ow*stride.  base() is non-decreasing in t,
-// so a tile of consecutive outputs touches one contiguous range of u.
+// base(t) = (n*Hp + oh*stride + border - pad)*Wp + ow*stride + border - pad.
+// base() is non-decreasing in t, so a tile of consecutive outputs touches one
+// contiguous range of u, and no tap of a valid output leaves the array.
 #pragma once
 
 namespace ebs {
 
 struct TileGeom {
-    int H, W, R, S, stride, pad, OH, OW;
-    int Hp() const { return H + 2 * pad; }
-    int Wp() const { return W + 2 * pad; }
+    int H, W, R, S, stride, pad, OH, OW, border;
+    int Hp() const { return H + 2 * border; }
+    int Wp() const { return W + 2 * border; }
     long long base(long long t) const
     {
         long long ow = t % OW;
         long long oh = (t / OW) % OH;
         long long n = t / ((long long)OW * OH);
-        return (n * Hp() + oh * stride) * Wp() + ow * stride;
+        return (n * Hp() + oh * stride + border - pad) * Wp() + ow * stride + border - pad;
     }
     // Exact extent (number of positions u) touched by outputs [t0, t1].
     long long extent(long long t0, long long t1) const

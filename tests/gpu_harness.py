@@ -78,15 +78,20 @@ def assert_f32_close(out, ref, acc_ref, scale, per_channel):
 
 
 def unpack_activations(words, N, H, W, C, k_a):
-    """Test-side inverse of the activation packing: uint32 [pixel][word][plane] -> levels."""
+    """Test-side inverse of the activation packing: uint32 [n][H+2][W+2][word][plane]
+    (one zero position all round every image, a few slack words at the very end)
+    -> (levels NHWC, channel-padding bits, border words)."""
     cw = (C + 31) // 32
-    w = np.asarray(words).view(np.uint32).reshape(N * H * W, cw, k_a)
-    bits = ((w[:, :, :, None] >> np.arange(32, dtype=np.uint32)) & 1).astype(np.uint8)  # pix, word, plane, bit
-    lv = np.zeros((N * H * W, cw, 32), np.uint8)
+    Hp, Wp = H + 2, W + 2
+    w = np.asarray(words).view(np.uint32)[:N * Hp * Wp * cw * k_a].reshape(N, Hp, Wp, cw, k_a)
+    inner = w[:, 1:-1, 1:-1]
+    border = np.concatenate([w[:, 0].reshape(-1), w[:, -1].reshape(-1), w[:, :, 0].reshape(-1), w[:, :, -1].reshape(-1)])
+    bits = ((inner[..., None] >> np.arange(32, dtype=np.uint32)) & 1).astype(np.uint8)   # n,h,w,word,plane,bit
+    lv = np.zeros((N, H, W, cw, 32), np.uint8)
     for j in range(k_a):
-        lv |= bits[:, :, j, :] << j
-    full = lv.reshape(N * H * W, cw * 32)
-    return full[:, :C].reshape(N, H, W, C), full[:, C:]
+        lv |= bits[..., j, :] << j
+    full = lv.reshape(N, H, W, cw * 32)
+    return full[..., :C], full[..., C:], border
 
 
 def unpack_weights(words, K, C, R, S, k_w):

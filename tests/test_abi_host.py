@@ -41,10 +41,10 @@ def test_version_and_status_strings(lib):
 
 
 def test_packed_sizes(lib):
-    # activations: N*H*W pixels x ceil(C/32) words x k_a planes x 4 bytes
-    assert ebs.ebs_packed_activations_bytes(64, 56, 56, 64, 4) == 64 * 56 * 56 * 2 * 4 * 4
-    assert ebs.ebs_packed_activations_bytes(1, 8, 8, 16, 2) == 64 * 1 * 2 * 4
-    assert ebs.ebs_packed_activations_bytes(1, 1, 1, 33, 1) == 2 * 4
+    # activations: N*(H+2)*(W+2) positions x ceil(C/32) words x k_a planes x 4 bytes + 16 slack bytes
+    assert ebs.ebs_packed_activations_bytes(64, 56, 56, 64, 4) == 64 * 58 * 58 * 2 * 4 * 4 + 16
+    assert ebs.ebs_packed_activations_bytes(1, 8, 8, 16, 2) == 100 * 1 * 2 * 4 + 16
+    assert ebs.ebs_packed_activations_bytes(1, 1, 1, 33, 1) == 9 * 2 * 4 + 16
     # weights: K rounded up to 16
     assert ebs.ebs_packed_weights_bytes(64, 64, 3, 3, 1) == 64 * 9 * 2 * 4
     assert ebs.ebs_packed_weights_bytes(1000, 2048, 1, 1, 4) == 1008 * 64 * 4 * 4
