@@ -18,6 +18,8 @@ static const char *const kNames[] = {
     "k4.tile64.ch2", "k4.tile64.ch1", "k4.tile64.ch4",
     "k4.tile32.ch2", "k4.tile32.ch1", "k4.tile32.ch4",
     "r4.tile128.ch4", "r4.tile64.ch4", "r4.tile32.ch4",
+    "k4.tile16.ch2", "k4.tile16.ch1", "k4.tile16.ch4",
+    "r4.tile16.ch4",
 };
 static constexpr int kNumVariants = sizeof(kNames) / sizeof(kNames[0]);
 
@@ -36,21 +38,37 @@ static int run_variant(const ConvArgs &a, int v)
     return EBS_ERR_BITWIDTH;
 }
 
-// Index of the variant with this chunk size inside a budget family (order ch2, ch1, ch4).
-static int ch_index(int cw) { return cw >= 4 ? 2 : (cw >= 2 ? 0 : 1); }
+// Variant index inside a (mode, budget) family of three: order ch2, ch1, ch4.
+static int ch_slot(int cw) { return cw % 4 == 0 ? 2 : (cw % 2 == 0 ? 0 : 1); }
+
+// Channels per wave of the (budget, shift classes) tiles; mirrors TileOf in the kernel header.
+static int kt_of(int budget, int ncls)
+{
+    static const int k128[7] = {32, 16, 8, 8, 4, 4, 4}, k64[7] = {16, 8, 8, 8, 4, 4, 4};
+    static const int k32[7] = {16, 8, 8, 8, 4, 4, 4}, k16[7] = {16, 8, 4, 4, 4, 4, 4};
+    const int *t = budget == 128 ? k128 : budget == 64 ? k64 : budget == 32 ? k32 : k16;
+    return t[ncls - 1];
+}
 
 int launch_conv_tiled(const ConvArgs &a, int variant)
 {
     if (variant >= 0) return run_variant(a, variant);
-    // Heuristic: few outputs with a long reduction -> split the reduction among the waves;
-    // otherwise the 64-register tile, falling back to smaller staging footprints.
-    long long outputs = (long long)a.N * a.OH * a.OW * a.K;
-    int order[5];
+    // Shape heuristic, from sweeps over ResNet-shaped layers on MI355X: small register tiles
+    // win (more, shorter work-groups balance the 1024 SIMDs and hide latency); the four waves
+    // of a work-group share one staged position tile and take four channel tiles (K4) when the
+    // layer has that many channels, and split the reduction (R4) when there are few output
+    // positions and a long reduction.
+    const long long positions = (long long)a.N * a.OH * a.OW;
+    const int ncls = a.kw + a.ka - 1;
+    const int slot = ch_slot(a.cw);
+    const int budget = ncls <= 2 ? 16 : 32;
+    int order[6];
     int n = 0;
-    if (outputs < (1 << 22) && a.cw >= 4) order[n++] = 19;
-    order[n++] = 3 + ch_index(a.cw);
-    order[n++] = 6 + ch_index(a.cw);
-    order[n++] = 7;
+    if (positions <= 4096 && a.cw >= 16 && a.cw % 4 == 0) order[n++] = 20;        // r4.tile32.ch4
+    if (a.K >= 4 * kt_of(budget, ncls)) order[n++] = (budget == 16 ? 21 : 15) + slot;   // k4.tile16 / k4.tile32
+    else if (a.K >= 4 * kt_of(16, ncls)) order[n++] = 21 + slot;
+    order[n++] = 6 + slot;        // p4.tile32
+    order[n++] = 7;               // p4.tile32.ch1: smallest staging footprint
     for (int i = 0; i < n; ++i) {
         int rc = run_variant(a, order[i]);
         if (rc != EBS_ERR_UNSUPPORTED) return rc;

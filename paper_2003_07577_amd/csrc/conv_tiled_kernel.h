@@ -17,6 +17,8 @@
 //    contiguous run of the flat zero-bordered input (see tile_geometry.h): the
 //    staging is a plain copy, image borders need no test and every filter tap
 //    is a wave-uniform LDS offset r*Wp + s.  Needs pad <= the stored border.
+//    LDS layout is [word][position][plane], so the lanes of a wave (consecutive
+//    positions) read consecutive addresses whatever the chunk size.
 //  * the four waves of a work-group either take four position sub-tiles of one
 //    channel tile (MODE_P4), four channel tiles of one position tile (MODE_K4:
 //    the staged activations serve 4*KT channels and the output rows a
@@ -75,7 +77,7 @@ struct Cfg {
     static constexpr int TPW = 64 * PIX;             // positions per wave
     static constexpr int TP = WPX * TPW;             // positions per work-group
     static constexpr int KB = WK * KT;               // channels per work-group
-    static constexpr int POSW = CH * KAP;            // LDS dwords per staged position
+    static constexpr int POSW = CH * KAP;            // LDS dwords per staged position (all words of the chunk)
     static constexpr int WSTEP = CH / WRED;          // reduction words per wave per tap per chunk
     static constexpr int KG = (KT + kWgtGroup - 1) / kWgtGroup;   // 16-channel weight groups per tile
     static constexpr int KTG = KT < kWgtGroup ? KT : kWgtGroup;   // channels taken from one group
@@ -127,7 +129,7 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
     for (int p = 0; p < PIX; ++p) {
         int t = t_first + wpx * C::TPW + p * 64 + lane;
         int tc = t < sh.total ? t : sh.total - 1;
-        my_lds[p] = (base_of(tc) - u_lo) * C::POSW;
+        my_lds[p] = (base_of(tc) - u_lo) * C::KAP;
     }
 
     // ---- staging of one reduction chunk: positions [u_lo, u_hi] of the bordered
@@ -154,7 +156,7 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
 #pragma unroll
                 for (int j = 0; j < C::KAP; ++j) vv[j] = v[j];
             }
-            *reinterpret_cast<vec_t *>(lds + (size_t)x * C::KAP) = vv;
+            *reinterpret_cast<vec_t *>(lds + (size_t)(w * sh.ucap + u) * C::KAP) = vv;
         }
     };
 
@@ -212,19 +214,20 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
 
         if (!(sh.dbg & 2)) {
             uint32_t xc[PIX][KA], qc[KT][KW];
-            const int w_first = wred * C::KAP;     // LDS dword offset of this wave's first word
-            int tap_off = 0;                       // (r*Wp + s) * POSW of the current tap
+            const int wstride = sh.ucap * C::KAP;  // LDS dwords between consecutive words of a position
+            const int w_first = wred * wstride;    // LDS dword offset of this wave's first word
+            int tap_off = 0;                       // (r*Wp + s) * KAP of the current tap
             int s_col = 0;
             int qoff = 0;
             fetch_q(0, qc);
             fetch_x(w_first, xc);
             for (int tap = 0; tap < sh.RS; ++tap) {
                 // LDS offset of the next tap
-                int next_off = tap_off + C::POSW;
+                int next_off = tap_off + C::KAP;
                 int next_col = s_col + 1;
                 if (next_col == sh.S) {
                     next_col = 0;
-                    next_off += (sh.Wp - sh.S) * C::POSW;
+                    next_off += (sh.Wp - sh.S) * C::KAP;
                 }
                 const bool more_taps = tap + 1 < sh.RS;
 #pragma unroll
@@ -240,7 +243,7 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
                     if (have_next) {
                         qoff += wrap ? q_wrap : QSTEP;
                         fetch_q(qoff, qn);
-                        fetch_x(wrap ? next_off + w_first : tap_off + w_first + (ws + 1) * C::WRED * C::KAP, xn);
+                        fetch_x(wrap ? next_off + w_first : tap_off + w_first + (ws + 1) * C::WRED * wstride, xn);
                     }
                     // ... then Eq. 2 / Eq. 13 on the current ones: AND + accumulating bitcount per plane pair
 #pragma unroll
@@ -364,6 +367,8 @@ EBS_TILE(64, 1, 4, 16)  EBS_TILE(64, 2, 4, 8)   EBS_TILE(64, 3, 2, 8)  EBS_TILE(
 EBS_TILE(64, 5, 2, 4)   EBS_TILE(64, 6, 2, 4)   EBS_TILE(64, 7, 2, 4)
 EBS_TILE(32, 1, 2, 16)  EBS_TILE(32, 2, 2, 8)   EBS_TILE(32, 3, 1, 8)  EBS_TILE(32, 4, 1, 8)
 EBS_TILE(32, 5, 1, 4)   EBS_TILE(32, 6, 1, 4)   EBS_TILE(32, 7, 1, 4)
+EBS_TILE(16, 1, 1, 16)  EBS_TILE(16, 2, 1, 8)   EBS_TILE(16, 3, 1, 4)  EBS_TILE(16, 4, 1, 4)
+EBS_TILE(16, 5, 1, 4)   EBS_TILE(16, 6, 1, 4)   EBS_TILE(16, 7, 1, 4)
 #undef EBS_TILE
 
 static constexpr size_t kMaxLdsBytes = 64 * 1024;
@@ -412,8 +417,10 @@ static int launch_cfg(const ConvArgs &a)
     X(9, 128, 2, MODE_K4)  X(10, 128, 1, MODE_K4) X(11, 128, 4, MODE_K4)    \
     X(12, 64, 2, MODE_K4)  X(13, 64, 1, MODE_K4)  X(14, 64, 4, MODE_K4)     \
     X(15, 32, 2, MODE_K4)  X(16, 32, 1, MODE_K4)  X(17, 32, 4, MODE_K4)     \
-    X(18, 128, 4, MODE_R4) X(19, 64, 4, MODE_R4)  X(20, 32, 4, MODE_R4)
-constexpr int kNumTiledVariants = 21;
+    X(18, 128, 4, MODE_R4) X(19, 64, 4, MODE_R4)  X(20, 32, 4, MODE_R4)     \
+    X(21, 16, 2, MODE_K4)  X(22, 16, 1, MODE_K4)  X(23, 16, 4, MODE_K4)     \
+    X(24, 16, 4, MODE_R4)
+constexpr int kNumTiledVariants = 25;
 
 template <int KW, int KA>
 static int launch_bits(const ConvArgs &a, int v)
