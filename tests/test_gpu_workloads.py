@@ -1,0 +1,63 @@
+"""GPU parity on the five workload families at their full sizes, in the launch
+configuration bench.py times (library heuristic, variant 0): every int32
+accumulator of every case is compared with the CPU oracle, fp32 outputs within
+1e-5 relative.  The oracle runs each full layer in well under a second on the
+host cores of the GPU machine, so no sampling is needed."""
+import time
+
+import numpy as np
+import pytest
+
+import ebs_workloads as wl
+from gpu_harness import POISON, assert_f32_close, run_case
+
+pytestmark = pytest.mark.gpu
+
+
+def _run_config(oracle_mod, cfg, N=None, keep=None):
+    cases = wl.config_cases(cfg, N)
+    t_start = time.time()
+    n_done = 0
+    for c in cases:
+        if keep is not None and not keep(c):
+            continue
+        L = c.layer
+        inp = wl.make_inputs(c)
+        acc, out, _ = run_case(inp, c.k_w, c.k_a, L.stride, L.pad, 0)
+        ref = oracle_mod.conv2d_levels(inp["a"], inp["q"], L.stride, L.pad)
+        assert acc.shape == ref.shape == (L.N, L.OH, L.OW, L.K)
+        assert not (acc == POISON).any(), f"{c.tag}: unwritten accumulators"
+        nbad = int((acc != ref).sum())
+        assert nbad == 0, f"{c.tag}: {nbad} of {ref.size} accumulators differ"
+        fref = oracle_mod.dequant(ref, inp["scale"], inp["offset"], inp["per_channel"])
+        assert_f32_close(out, fref, ref, inp["scale"], inp["per_channel"])
+        n_done += 1
+        print(f"[ok] {c.tag} ({time.time() - t_start:.1f}s)", flush=True)
+    assert n_done > 0
+
+
+def test_config2_cifar_resnet20_stack(oracle_mod):
+    _run_config(oracle_mod, 2)
+
+
+@pytest.mark.parametrize("layer_index", range(7))
+def test_config3_resnet18_layers_all_bit_pairs(oracle_mod, layer_index):
+    _run_config(oracle_mod, 3, keep=lambda c: c.layer_index == layer_index)
+
+
+def test_config4_resnet50_bottlenecks(oracle_mod):
+    _run_config(oracle_mod, 4)
+
+
+def test_config5_fully_connected(oracle_mod):
+    _run_config(oracle_mod, 5)
+
+
+def test_config3_activation_level_distribution():
+    """The clipped half-normal recipe fills the low levels more than the high ones and
+    never exceeds the bitwidth (host check of the generator, cheap)."""
+    c = [x for x in wl.config_cases(3, N=2) if x.layer_index == 0 and (x.k_w, x.k_a) == (2, 3)][0]
+    a = wl.make_inputs(c)["a"]
+    assert a.max() <= 7
+    hist = np.bincount(a.reshape(-1), minlength=8)
+    assert hist[1] > hist[6] > 0
