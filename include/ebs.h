@@ -127,7 +127,7 @@ int ebs_mixed_conv2d_variant(int variant,
  * Measured comparison only (not the binary-decomposition path): the same
  * integer convolution taken directly on the unpacked levels with int8 matrix
  * instructions.  Same outputs and conventions as ebs_mixed_conv2d; needs
- * C to be a multiple of 16 (EBS_ERR_UNSUPPORTED otherwise); levels must be
+ * C to be a multiple of 32 (EBS_ERR_UNSUPPORTED otherwise); levels must be
  * below 128.
  */
 int ebs_mixed_conv2d_mfma_i8(const uint8_t *act_levels_nhwc, const uint8_t *wgt_levels_krsc,

@@ -49,4 +49,5 @@ def build_library(jobs: int = 8, extra=()) -> str:
 
 
 if __name__ == "__main__":
-    print(build_library())
+    # EBS_BUILD_EXTRA="-DEBS_EXPERIMENT" builds the phase-timing experiment variant
+    print(build_library(extra=tuple(os.environ.get("EBS_BUILD_EXTRA", "").split())))

@@ -37,6 +37,14 @@ namespace ebs {
 
 enum { MODE_P4 = 0, MODE_K4 = 1, MODE_R4 = 2 };
 
+// Experiment builds (-DEBS_EXPERIMENT) can switch phases of the kernel off through the
+// EBS_EXP_DBG environment variable to time them; production builds compile this away.
+#ifdef EBS_EXPERIMENT
+#define EBS_DBG(bit) (sh.dbg & (bit))
+#else
+#define EBS_DBG(bit) false
+#endif
+
 struct TiledShape {
     int N, H, W, K, R, S, stride, pad, OH, OW, cw, Hp, Wp, RS;   // Hp, Wp: bordered grid
     int total;        // N*OH*OW output positions
@@ -45,7 +53,7 @@ struct TiledShape {
     int ucap;         // staged positions that fit the LDS allocation
     int wgroups;      // 16-channel groups present in the packed weights
     int stage_dwords; // LDS dwords reserved for staged activations (the output tile follows)
-    int dbg;          // experiment switches (0 in production)
+    int dbg;          // experiment switches; only read in EBS_EXPERIMENT builds
 };
 
 template <int N> struct UVec;
@@ -101,6 +109,9 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
     extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
     int32_t *otile = reinterpret_cast<int32_t *>(lds + sh.stage_dwords);
 
+#ifdef EBS_EXPERIMENT
+    const unsigned long long exp_t0 = wall_clock64();
+#endif
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -212,7 +223,7 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
             }
         };
 
-        if (!(sh.dbg & 2)) {
+        if (!EBS_DBG(2)) {
             uint32_t xc[PIX][KA], qc[KT][KW];
             const int wstride = sh.ucap * C::KAP;  // LDS dwords between consecutive words of a position
             const int w_first = wred * wstride;    // LDS dword offset of this wave's first word
@@ -326,7 +337,7 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
             }
         }
         __syncthreads();
-        if (sh.dbg & 1) continue;
+        if (EBS_DBG(1)) continue;
         // rows of this pass: row r of sub-tile w is position t_first + w*TPW + p*64 + r
 #pragma unroll
         for (int r0 = 0; r0 < C::OROWS; r0 += RSTEP) {
@@ -337,7 +348,7 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
                 const size_t o = (size_t)t * sh.K + kq;
                 if (vec_ok) {
                     *reinterpret_cast<i32x4 *>(acc_out + o) = v;
-                    if (out_f32) {
+                    if (out_f32 && !EBS_DBG(8)) {
                         f32x4 f = {fmaf((float)v[0], sc[0], of[0]), fmaf((float)v[1], sc[1], of[1]),
                                    fmaf((float)v[2], sc[2], of[2]), fmaf((float)v[3], sc[3], of[3])};
                         *reinterpret_cast<f32x4 *>(out_f32 + o) = f;
@@ -347,13 +358,20 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
                     for (int e = 0; e < 4; ++e) {
                         if (kq + e < sh.K) {
                             acc_out[o + e] = v[e];
-                            if (out_f32) out_f32[o + e] = fmaf((float)v[e], sc[e], of[e]);
+                            if (out_f32 && !EBS_DBG(8)) out_f32[o + e] = fmaf((float)v[e], sc[e], of[e]);
                         }
                     }
                 }
             }
         }
     }
+#ifdef EBS_EXPERIMENT
+    if (EBS_DBG(8) && out_f32 && tid == 0) {
+        unsigned long long *tr = reinterpret_cast<unsigned long long *>(out_f32) + 2 * ((size_t)blockIdx.y * gridDim.x + blockIdx.x);
+        tr[0] = exp_t0;
+        tr[1] = wall_clock64();
+    }
+#endif
 }
 
 // ------------------------------------------------------------------ launch
@@ -398,7 +416,9 @@ static int launch_cfg(const ConvArgs &a)
     if (lds_bytes > kMaxLdsBytes || ucap > (1 << 28)) return EBS_ERR_UNSUPPORTED;
     sh.ucap = (int)ucap;
     sh.stage_dwords = (int)stage_dwords;
+#ifdef EBS_EXPERIMENT
     if (const char *e = getenv("EBS_EXP_DBG")) sh.dbg = atoi(e);
+#endif
 
     long long ptiles = ((long long)sh.total + C::TP - 1) / C::TP;
     long long kblocks = ((long long)a.K + C::KB - 1) / C::KB;

@@ -205,3 +205,32 @@ def test_nondefault_stream(oracle_mod):
     conv(d, 0, s)
     s.synchronize()
     assert np.array_equal(d["acc"].cpu().numpy(), oracle_mod.conv2d_levels(inp["a"], inp["q"], 1, 1))
+
+
+# ------------------------------------------------------------------ int8 matrix-core comparison path
+def test_mfma_i8_comparison_matches_oracle(oracle_mod):
+    import torch
+    dev = torch.device("cuda:0")
+    geos = [  # N, C, H, W, K, R, S, stride, pad
+        (2, 64, 20, 20, 40, 3, 3, 1, 1), (3, 96, 9, 11, 130, 3, 3, 2, 1), (1, 32, 13, 7, 5, 1, 1, 1, 0),
+        (2, 128, 8, 8, 64, 3, 3, 1, 1), (1, 256, 7, 7, 70, 3, 3, 1, 1), (2, 64, 10, 9, 33, 3, 2, 3, 0),
+    ]
+    for gi, (N, C, H, W, K, R, S, st, pad) in enumerate(geos):
+        inp = wl.random_case(4000 + gi, N, C, H, W, K, R, S, st, pad, 4, 4, per_channel=(gi % 2 == 0), with_offset=True)
+        print(f"[case] mfma geo{gi}", flush=True)
+        OH, OW = ebs.out_dims(H, W, R, S, st, pad)
+        a = torch.from_numpy(inp["a"]).to(dev)
+        q = torch.from_numpy(inp["q"]).to(dev)
+        sc = torch.from_numpy(inp["scale"]).to(dev)
+        of = torch.from_numpy(inp["offset"]).to(dev)
+        acc = torch.full((N, OH, OW, K), POISON, dtype=torch.int32, device=dev)
+        out = torch.full((N, OH, OW, K), float("nan"), dtype=torch.float32, device=dev)
+        ebs.ebs_mixed_conv2d_mfma_i8(a, q, N, C, H, W, K, R, S, st, pad, sc, of, inp["per_channel"], acc, out)
+        torch.cuda.synchronize()
+        ref = oracle_mod.conv2d_levels(inp["a"], inp["q"], st, pad)
+        assert np.array_equal(acc.cpu().numpy(), ref), gi
+        fref = oracle_mod.dequant(ref, inp["scale"], inp["offset"], inp["per_channel"])
+        assert_f32_close(out.cpu().numpy(), fref, ref, inp["scale"], inp["per_channel"])
+    # unsupported channel count is an error code, not a crash
+    rc = ebs.ebs_mixed_conv2d_mfma_i8(a, q, 1, 16, 4, 4, 8, 3, 3, 1, 1, sc, None, 0, acc, out, None, check=False)
+    assert rc == -5
