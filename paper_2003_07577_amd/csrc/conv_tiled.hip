@@ -1,52 +1,58 @@
 // Variant table and shape heuristic of the tiled convolution; the kernels are
-// instantiated per weight bitwidth in conv_tiled_kw*.hip.
+// instantiated per (weight bitwidth, filter specialisation) in conv_tiled_kw*_f*.hip.
 #include "ebs_internal.h"
 
 namespace ebs {
 
-template <int KW> int launch_tiled_kw(const ConvArgs &a, int v);
-template <> int launch_tiled_kw<1>(const ConvArgs &a, int v);
-template <> int launch_tiled_kw<2>(const ConvArgs &a, int v);
-template <> int launch_tiled_kw<3>(const ConvArgs &a, int v);
-template <> int launch_tiled_kw<4>(const ConvArgs &a, int v);
+template <int KW, int FS> int launch_tiled_kw(const ConvArgs &a, int v);
+#define EBS_DECL(kw) \
+    template <> int launch_tiled_kw<kw, 0>(const ConvArgs &a, int v); \
+    template <> int launch_tiled_kw<kw, 3>(const ConvArgs &a, int v);
+EBS_DECL(1) EBS_DECL(2) EBS_DECL(3) EBS_DECL(4)
+#undef EBS_DECL
 
+// Order must match EBS_TILED_VARIANTS in conv_tiled_kernel.h.
 static const char *const kNames[] = {
-    "p4.tile128.ch2", "p4.tile128.ch1", "p4.tile128.ch4",
     "p4.tile64.ch2", "p4.tile64.ch1", "p4.tile64.ch4",
     "p4.tile32.ch2", "p4.tile32.ch1", "p4.tile32.ch4",
-    "k4.tile128.ch2", "k4.tile128.ch1", "k4.tile128.ch4",
     "k4.tile64.ch2", "k4.tile64.ch1", "k4.tile64.ch4",
     "k4.tile32.ch2", "k4.tile32.ch1", "k4.tile32.ch4",
-    "r4.tile128.ch4", "r4.tile64.ch4", "r4.tile32.ch4",
     "k4.tile16.ch2", "k4.tile16.ch1", "k4.tile16.ch4",
-    "r4.tile16.ch4",
+    "r4.tile64.ch4", "r4.tile32.ch4", "r4.tile16.ch4",
 };
 static constexpr int kNumVariants = sizeof(kNames) / sizeof(kNames[0]);
+enum { V_P4_64 = 0, V_P4_32 = 3, V_K4_64 = 6, V_K4_32 = 9, V_K4_16 = 12, V_R4_64 = 15, V_R4_32 = 16, V_R4_16 = 17 };
 
 int conv_tiled_variant_count() { return kNumVariants; }
 const char *conv_tiled_variant_name(int v) { return (v >= 0 && v < kNumVariants) ? kNames[v] : "invalid"; }
 
-static int run_variant(const ConvArgs &a, int v)
+template <int FS>
+static int run_fs(const ConvArgs &a, int v)
 {
-    if (v < 0 || v >= kNumVariants) return EBS_ERR_UNSUPPORTED;
     switch (a.kw) {
-        case 1: return launch_tiled_kw<1>(a, v);
-        case 2: return launch_tiled_kw<2>(a, v);
-        case 3: return launch_tiled_kw<3>(a, v);
-        case 4: return launch_tiled_kw<4>(a, v);
+        case 1: return launch_tiled_kw<1, FS>(a, v);
+        case 2: return launch_tiled_kw<2, FS>(a, v);
+        case 3: return launch_tiled_kw<3, FS>(a, v);
+        case 4: return launch_tiled_kw<4, FS>(a, v);
     }
     return EBS_ERR_BITWIDTH;
 }
 
-// Variant index inside a (mode, budget) family of three: order ch2, ch1, ch4.
+static int run_variant(const ConvArgs &a, int v)
+{
+    if (v < 0 || v >= kNumVariants) return EBS_ERR_UNSUPPORTED;
+    if (a.R == 3 && a.S == 3) return run_fs<3>(a, v);     // unrolled 3x3 taps
+    return run_fs<0>(a, v);
+}
+
+// Slot of the chunk size inside a family of three: order ch2, ch1, ch4.
 static int ch_slot(int cw) { return cw % 4 == 0 ? 2 : (cw % 2 == 0 ? 0 : 1); }
 
 // Channels per wave of the (budget, shift classes) tiles; mirrors TileOf in the kernel header.
 static int kt_of(int budget, int ncls)
 {
-    static const int k128[7] = {32, 16, 8, 8, 4, 4, 4}, k64[7] = {16, 8, 8, 8, 4, 4, 4};
-    static const int k32[7] = {16, 8, 8, 8, 4, 4, 4}, k16[7] = {16, 8, 4, 4, 4, 4, 4};
-    const int *t = budget == 128 ? k128 : budget == 64 ? k64 : budget == 32 ? k32 : k16;
+    static const int k64[7] = {16, 8, 8, 8, 4, 4, 4}, k32[7] = {16, 8, 8, 8, 4, 4, 4}, k16[7] = {16, 8, 4, 4, 4, 4, 4};
+    const int *t = budget == 64 ? k64 : budget == 32 ? k32 : k16;
     return t[ncls - 1];
 }
 
@@ -64,11 +70,11 @@ int launch_conv_tiled(const ConvArgs &a, int variant)
     const int budget = ncls <= 2 ? 16 : 32;
     int order[6];
     int n = 0;
-    if (positions <= 4096 && a.cw >= 16 && a.cw % 4 == 0) order[n++] = 20;        // r4.tile32.ch4
-    if (a.K >= 4 * kt_of(budget, ncls)) order[n++] = (budget == 16 ? 21 : 15) + slot;   // k4.tile16 / k4.tile32
-    else if (a.K >= 4 * kt_of(16, ncls)) order[n++] = 21 + slot;
-    order[n++] = 6 + slot;        // p4.tile32
-    order[n++] = 7;               // p4.tile32.ch1: smallest staging footprint
+    if (positions <= 4096 && a.cw >= 16 && a.cw % 4 == 0) order[n++] = V_R4_32;
+    if (a.K >= 4 * kt_of(budget, ncls)) order[n++] = (budget == 16 ? V_K4_16 : V_K4_32) + slot;
+    else if (a.K >= 4 * kt_of(16, ncls)) order[n++] = V_K4_16 + slot;
+    order[n++] = V_P4_32 + slot;
+    order[n++] = V_P4_32 + 1;       // ch1: smallest staging footprint
     for (int i = 0; i < n; ++i) {
         int rc = run_variant(a, order[i]);
         if (rc != EBS_ERR_UNSUPPORTED) return rc;

@@ -25,11 +25,17 @@
 //    work-group writes are 4*KT channels wide), or four shares of the reduction
 //    words of one tile (MODE_R4, for layers with few outputs and a long
 //    reduction; the partial sums meet in LDS).
+//  * FS = 3 instantiates the 3x3 filter with the taps of a filter row unrolled
+//    (tap offsets become instruction immediates); FS = 0 is the generic filter.
 //  * the epilogue goes through LDS: accumulators are laid out [position][channel]
 //    and written back by all 256 threads as 16-byte pieces of consecutive
 //    addresses, so global stores cover whole runs of each NHWC output row.
+//  * work-groups are numbered so that the eight accelerator dies (work-groups
+//    are dealt to them round-robin) each take one contiguous eighth of the
+//    position tiles: a die's L2 then only ever sees its own part of the input.
 #pragma once
 #include "ebs_internal.h"
+#include "fastdiv.h"
 #include "tile_geometry.h"
 #include <cstdlib>
 
@@ -46,13 +52,17 @@ enum { MODE_P4 = 0, MODE_K4 = 1, MODE_R4 = 2 };
 #endif
 
 struct TiledShape {
-    int N, H, W, K, R, S, stride, pad, OH, OW, cw, Hp, Wp, RS;   // Hp, Wp: bordered grid
+    int K, R, S, stride, pad, OW, cw, Hp, Wp, RS;   // Hp, Wp: bordered grid
     int total;        // N*OH*OW output positions
-    int nchunks;      // ceil(cw / CH) reduction chunks staged one at a time
+    int nchunks;      // cw / CH reduction chunks staged one at a time
     int per_channel;
     int ucap;         // staged positions that fit the LDS allocation
     int wgroups;      // 16-channel groups present in the packed weights
     int stage_dwords; // LDS dwords reserved for staged activations (the output tile follows)
+    int kblocks;      // channel blocks per position tile
+    int nblocks;      // position tiles * channel blocks
+    int xcd_chunk;    // ceil(nblocks / 8): logical blocks handled by one die
+    FastDiv div_ow, div_ohow, div_kblocks;
     int dbg;          // experiment switches; only read in EBS_EXPERIMENT builds
 };
 
@@ -99,7 +109,7 @@ struct Cfg {
     static_assert(256 % (OCOLS / 4) == 0, "write-back assumes a fixed column group per thread");
 };
 
-template <int KW, int KA, int PIX, int KT, int CH, int MODE>
+template <int KW, int KA, int PIX, int KT, int CH, int MODE, int FS>
 __global__ void __launch_bounds__(256)
 bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
               const float *__restrict__ scale, const float *__restrict__ offset,
@@ -108,31 +118,42 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
     using C = Cfg<KW, KA, PIX, KT, CH, MODE>;
     extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
     int32_t *otile = reinterpret_cast<int32_t *>(lds + sh.stage_dwords);
-
 #ifdef EBS_EXPERIMENT
     const unsigned long long exp_t0 = wall_clock64();
 #endif
+
+    // ---- which (position tile, channel block): dies take contiguous runs of logical blocks
+    const int die = blockIdx.x & 7;
+    const int slot = blockIdx.x >> 3;
+    const int logical = die * sh.xcd_chunk + slot;
+    if (slot >= sh.xcd_chunk || logical >= sh.nblocks) return;       // uniform for the whole work-group
+    const int ptile = (int)fd_div((uint32_t)logical, sh.div_kblocks);
+    const int kblock = logical - ptile * sh.kblocks;
+
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wpx = MODE == MODE_P4 ? wave : 0;     // position sub-tile of this wave
     const int wk = MODE == MODE_K4 ? wave : 0;      // channel sub-tile of this wave
     const int wred = MODE == MODE_R4 ? wave : 0;    // share of the reduction words
+    const int R = FS > 0 ? FS : sh.R;
+    const int S = FS > 0 ? FS : sh.S;
+    const int RS = FS > 0 ? FS * FS : sh.RS;
 
     // ---- tile of output positions and the flat bordered-input range it reads
-    const int t_first = blockIdx.x * C::TP;
+    const int t_first = ptile * C::TP;
     int t_last = t_first + C::TP - 1;
     if (t_last > sh.total - 1) t_last = sh.total - 1;
-    const int ohow = sh.OH * sh.OW;
+    const int origin = kActBorder - sh.pad;
     auto base_of = [&](int t) {
-        int n = t / ohow;
-        int rem = t - n * ohow;
-        int oh = rem / sh.OW;
-        int ow = rem - oh * sh.OW;
-        return (n * sh.Hp + oh * sh.stride + kActBorder - sh.pad) * sh.Wp + ow * sh.stride + kActBorder - sh.pad;
+        const int n = (int)fd_div((uint32_t)t, sh.div_ohow);
+        const int rem = t - n * (int)sh.div_ohow.d;
+        const int oh = (int)fd_div((uint32_t)rem, sh.div_ow);
+        const int ow = rem - oh * sh.OW;
+        return (n * sh.Hp + oh * sh.stride + origin) * sh.Wp + ow * sh.stride + origin;
     };
     const int u_lo = base_of(t_first);
-    int u_hi = base_of(t_last) + (sh.R - 1) * sh.Wp + (sh.S - 1);
+    int u_hi = base_of(t_last) + (R - 1) * sh.Wp + (S - 1);
     if (u_hi > u_lo + sh.ucap - 1) u_hi = u_lo + sh.ucap - 1;   // never beyond the LDS allocation
 
     int my_lds[PIX];          // LDS dword index of the lane's positions (tap 0, word 0)
@@ -147,31 +168,24 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
     //      input are contiguous in memory; copy CH words (x KA planes) of each
     const int n_stage = (u_hi - u_lo + 1) * CH;
     auto stage = [&](int chunk) {
-        const int w0 = chunk * CH;
+        const unsigned src0 = ((unsigned)u_lo * sh.cw + chunk * CH) * KA;     // dword index, < 2^31
         for (int x = tid; x < n_stage; x += 256) {
             const int u = x / CH;
             const int w = x - u * CH;
-            uint32_t v[C::KAP];
-#pragma unroll
-            for (int j = 0; j < C::KAP; ++j) v[j] = 0u;
-            if (w0 + w < sh.cw) {
-                const uint32_t *src = act + ((size_t)(u_lo + u) * sh.cw + (w0 + w)) * KA;
-#pragma unroll
-                for (int j = 0; j < KA; ++j) v[j] = src[j];
-            }
+            const uint32_t *src = act + (src0 + ((unsigned)u * sh.cw + w) * KA);
             typedef typename UVec<C::KAP>::type vec_t;
             vec_t vv;
             if constexpr (C::KAP == 1) {
-                vv = v[0];
+                vv = src[0];
             } else {
 #pragma unroll
-                for (int j = 0; j < C::KAP; ++j) vv[j] = v[j];
+                for (int j = 0; j < C::KAP; ++j) vv[j] = j < KA ? src[j] : 0u;
             }
-            *reinterpret_cast<vec_t *>(lds + (size_t)(w * sh.ucap + u) * C::KAP) = vv;
+            *reinterpret_cast<vec_t *>(lds + (w * sh.ucap + u) * C::KAP) = vv;
         }
     };
 
-    const int kb0 = blockIdx.y * C::KB;       // first channel of the work-group
+    const int kb0 = kblock * C::KB;           // first channel of the work-group
     const int k0 = kb0 + wk * KT;             // first channel of this wave
     const int g0 = k0 / kWgtGroup;
 
@@ -183,10 +197,14 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
 #pragma unroll
             for (int s = 0; s < C::NCLS; ++s) cls[p][c][s] = 0u;
 
+    const int wstride = sh.ucap * C::KAP;     // LDS dwords between consecutive words of a position
+    const int rowstride = sh.Wp * C::KAP;     // LDS dwords between filter rows
+
     for (int chunk = 0; chunk < sh.nchunks; ++chunk) {
         if (chunk > 0) __syncthreads();       // everyone is done with the previous chunk
         stage(chunk);
         __syncthreads();
+        if (EBS_DBG(2)) continue;
 
         // weight words of this tile: [k/16][tap][word][k%16][plane]; per 16-channel group a
         // wave-uniform base pointer, plus one running offset over (tap, word)
@@ -195,7 +213,7 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
         for (int g = 0; g < C::KG; ++g) {
             // a tile may reach past the last packed group (its channels are never stored): re-read the last one
             const int gi = g0 + g < sh.wgroups ? g0 + g : sh.wgroups - 1;
-            wg[g] = wgt + ((size_t)gi * sh.RS * sh.cw + (size_t)chunk * CH + wred) * (kWgtGroup * KW)
+            wg[g] = wgt + ((size_t)gi * RS * sh.cw + (size_t)chunk * CH + wred) * (kWgtGroup * KW)
                         + (k0 % kWgtGroup) * KW;
         }
         constexpr int QSTEP = C::WRED * kWgtGroup * KW;                           // next word of this wave
@@ -209,73 +227,115 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
 #pragma unroll
                     for (int i = 0; i < KW; ++i) q[g * kWgtGroup + c][i] = wg[g][qoff + c * KW + i];
         };
-        auto fetch_x = [&](int off, uint32_t (&x)[PIX][KA]) {     // off: LDS dwords from the lane's position
+        auto load_x = [&](int idx, uint32_t (&x)[KA]) {          // idx: LDS dword index
+            typedef typename UVec<C::KAP>::type vec_t;
+            const vec_t v = *reinterpret_cast<const vec_t *>(lds + idx);
+            if constexpr (C::KAP == 1) {
+                x[0] = v;
+            } else {
 #pragma unroll
-            for (int p = 0; p < PIX; ++p) {
-                typedef typename UVec<C::KAP>::type vec_t;
-                const vec_t v = *reinterpret_cast<const vec_t *>(lds + my_lds[p] + off);
-                if constexpr (C::KAP == 1) {
-                    x[p][0] = v;
-                } else {
-#pragma unroll
-                    for (int j = 0; j < KA; ++j) x[p][j] = v[j];
-                }
+                for (int j = 0; j < KA; ++j) x[j] = v[j];
             }
         };
+        // Eq. 2 / Eq. 13 on one reduction word: AND + accumulating bitcount per plane pair
+        auto mac = [&](const uint32_t (&x)[PIX][KA], const uint32_t (&q)[KT][KW]) {
+#pragma unroll
+            for (int p = 0; p < PIX; ++p)
+#pragma unroll
+                for (int c = 0; c < KT; ++c)
+#pragma unroll
+                    for (int i = 0; i < KW; ++i)
+#pragma unroll
+                        for (int j = 0; j < KA; ++j)
+                            cls[p][c][i + j] = bcnt_acc(q[c][i] & x[p][j], cls[p][c][i + j]);
+        };
+        auto rotate = [&](uint32_t (&xc)[PIX][KA], uint32_t (&qc)[KT][KW],
+                          const uint32_t (&xn)[PIX][KA], const uint32_t (&qn)[KT][KW]) {
+#pragma unroll
+            for (int p = 0; p < PIX; ++p)
+#pragma unroll
+                for (int j = 0; j < KA; ++j) xc[p][j] = xn[p][j];
+#pragma unroll
+            for (int c = 0; c < KT; ++c)
+#pragma unroll
+                for (int i = 0; i < KW; ++i) qc[c][i] = qn[c][i];
+        };
 
-        if (!EBS_DBG(2)) {
-            uint32_t xc[PIX][KA], qc[KT][KW];
-            const int wstride = sh.ucap * C::KAP;  // LDS dwords between consecutive words of a position
+        uint32_t xc[PIX][KA], qc[KT][KW];
+        int qoff = 0;
+        fetch_q(0, qc);
+
+        if constexpr (FS > 0) {
+            // ---- fixed FS x FS filter: per filter row one LDS address per (position, word);
+            //      the taps of the row are instruction immediates
+            int addr[PIX][C::WSTEP];
+#pragma unroll
+            for (int p = 0; p < PIX; ++p)
+#pragma unroll
+                for (int ws = 0; ws < C::WSTEP; ++ws) addr[p][ws] = my_lds[p] + (ws * C::WRED + wred) * wstride;
+#pragma unroll
+            for (int p = 0; p < PIX; ++p) load_x(addr[p][0], xc[p]);
+            for (int r = 0; r < FS; ++r) {
+                const bool more_rows = r + 1 < FS;
+#pragma unroll
+                for (int s = 0; s < FS; ++s) {
+#pragma unroll
+                    for (int ws = 0; ws < C::WSTEP; ++ws) {
+                        const bool last_in_row = (s + 1 == FS) && (ws + 1 == C::WSTEP);
+                        const bool wrap = ws + 1 == C::WSTEP;          // next step starts a new tap
+                        const bool have_next = !last_in_row || more_rows;
+                        // The current operands were requested a whole step ago: wait for them BEFORE
+                        // the next requests go out (LDS and scalar loads share one counter that can
+                        // only be waited to zero, so a wait placed later would also cover the new ones).
+                        __builtin_amdgcn_s_waitcnt(0xC07F);     // lgkmcnt(0) only
+                        uint32_t xn[PIX][KA], qn[KT][KW];
+                        if (have_next) {
+                            qoff += wrap ? q_wrap : QSTEP;
+                            fetch_q(qoff, qn);
+                            const int nws = wrap ? 0 : ws + 1;
+                            const int noff = last_in_row ? rowstride : (wrap ? (s + 1) * C::KAP : s * C::KAP);
+#pragma unroll
+                            for (int p = 0; p < PIX; ++p) load_x(addr[p][nws] + noff, xn[p]);
+                        }
+                        mac(xc, qc);
+                        if (have_next) rotate(xc, qc, xn, qn);
+                    }
+                }
+#pragma unroll
+                for (int p = 0; p < PIX; ++p)
+#pragma unroll
+                    for (int ws = 0; ws < C::WSTEP; ++ws) addr[p][ws] += rowstride;
+            }
+        } else {
+            // ---- generic filter: one LDS offset per tap, maintained incrementally
             const int w_first = wred * wstride;    // LDS dword offset of this wave's first word
             int tap_off = 0;                       // (r*Wp + s) * KAP of the current tap
             int s_col = 0;
-            int qoff = 0;
-            fetch_q(0, qc);
-            fetch_x(w_first, xc);
-            for (int tap = 0; tap < sh.RS; ++tap) {
-                // LDS offset of the next tap
+#pragma unroll
+            for (int p = 0; p < PIX; ++p) load_x(my_lds[p] + w_first, xc[p]);
+            for (int tap = 0; tap < RS; ++tap) {
                 int next_off = tap_off + C::KAP;
                 int next_col = s_col + 1;
-                if (next_col == sh.S) {
+                if (next_col == S) {
                     next_col = 0;
-                    next_off += (sh.Wp - sh.S) * C::KAP;
+                    next_off += (sh.Wp - S) * C::KAP;
                 }
-                const bool more_taps = tap + 1 < sh.RS;
+                const bool more_taps = tap + 1 < RS;
 #pragma unroll
                 for (int ws = 0; ws < C::WSTEP; ++ws) {
                     const bool wrap = ws + 1 == C::WSTEP;      // known at compile time after unrolling
-                    // request the operands of the following step first ...
-                    uint32_t xn[PIX][KA], qn[KT][KW];
                     const bool have_next = !wrap || more_taps;
-                    // The current operands were requested a whole step ago: wait for them BEFORE
-                    // the next requests go out (LDS and scalar loads share one counter that can
-                    // only be waited to zero, so a wait placed later would also cover the new ones).
-                    __builtin_amdgcn_s_waitcnt(0xC07F);     // lgkmcnt(0) only
+                    __builtin_amdgcn_s_waitcnt(0xC07F);        // lgkmcnt(0) only, see above
+                    uint32_t xn[PIX][KA], qn[KT][KW];
                     if (have_next) {
                         qoff += wrap ? q_wrap : QSTEP;
                         fetch_q(qoff, qn);
-                        fetch_x(wrap ? next_off + w_first : tap_off + w_first + (ws + 1) * C::WRED * wstride, xn);
+                        const int off = wrap ? next_off + w_first : tap_off + w_first + (ws + 1) * C::WRED * wstride;
+#pragma unroll
+                        for (int p = 0; p < PIX; ++p) load_x(my_lds[p] + off, xn[p]);
                     }
-                    // ... then Eq. 2 / Eq. 13 on the current ones: AND + accumulating bitcount per plane pair
-#pragma unroll
-                    for (int p = 0; p < PIX; ++p)
-#pragma unroll
-                        for (int c = 0; c < KT; ++c)
-#pragma unroll
-                            for (int i = 0; i < KW; ++i)
-#pragma unroll
-                                for (int j = 0; j < KA; ++j)
-                                    cls[p][c][i + j] = bcnt_acc(qc[c][i] & xc[p][j], cls[p][c][i + j]);
-                    if (have_next) {
-#pragma unroll
-                        for (int p = 0; p < PIX; ++p)
-#pragma unroll
-                            for (int j = 0; j < KA; ++j) xc[p][j] = xn[p][j];
-#pragma unroll
-                        for (int c = 0; c < KT; ++c)
-#pragma unroll
-                            for (int i = 0; i < KW; ++i) qc[c][i] = qn[c][i];
-                    }
+                    mac(xc, qc);
+                    if (have_next) rotate(xc, qc, xn, qn);
                 }
                 tap_off = next_off;
                 s_col = next_col;
@@ -367,7 +427,7 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
     }
 #ifdef EBS_EXPERIMENT
     if (EBS_DBG(8) && out_f32 && tid == 0) {
-        unsigned long long *tr = reinterpret_cast<unsigned long long *>(out_f32) + 2 * ((size_t)blockIdx.y * gridDim.x + blockIdx.x);
+        unsigned long long *tr = reinterpret_cast<unsigned long long *>(out_f32) + 2 * (size_t)logical;
         tr[0] = exp_t0;
         tr[1] = wall_clock64();
     }
@@ -379,8 +439,6 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
 // (PIX, KT) per accumulator budget and number of shift classes.
 template <int BUDGET, int NCLS> struct TileOf;
 #define EBS_TILE(b, n, p, k) template <> struct TileOf<b, n> { static constexpr int PIX = p, KT = k; };
-EBS_TILE(128, 1, 4, 32) EBS_TILE(128, 2, 4, 16) EBS_TILE(128, 3, 4, 8) EBS_TILE(128, 4, 4, 8)
-EBS_TILE(128, 5, 4, 4)  EBS_TILE(128, 6, 4, 4)  EBS_TILE(128, 7, 4, 4)
 EBS_TILE(64, 1, 4, 16)  EBS_TILE(64, 2, 4, 8)   EBS_TILE(64, 3, 2, 8)  EBS_TILE(64, 4, 2, 8)
 EBS_TILE(64, 5, 2, 4)   EBS_TILE(64, 6, 2, 4)   EBS_TILE(64, 7, 2, 4)
 EBS_TILE(32, 1, 2, 16)  EBS_TILE(32, 2, 2, 8)   EBS_TILE(32, 3, 1, 8)  EBS_TILE(32, 4, 1, 8)
@@ -389,9 +447,11 @@ EBS_TILE(16, 1, 1, 16)  EBS_TILE(16, 2, 1, 8)   EBS_TILE(16, 3, 1, 4)  EBS_TILE(
 EBS_TILE(16, 5, 1, 4)   EBS_TILE(16, 6, 1, 4)   EBS_TILE(16, 7, 1, 4)
 #undef EBS_TILE
 
-static constexpr size_t kMaxLdsBytes = 64 * 1024;
+static constexpr size_t kMaxLdsBytes = 64 * 1024;       // per work-group (dynamic LDS without opt-in)
+static constexpr size_t kLdsPerCu = 160 * 1024;         // gfx950
+static constexpr int kNumCus = 256;
 
-template <int KW, int KA, int BUDGET, int CH, int MODE>
+template <int KW, int KA, int BUDGET, int CH, int MODE, int FS>
 static int launch_cfg(const ConvArgs &a)
 {
     constexpr int PIX = TileOf<BUDGET, KW + KA - 1>::PIX;
@@ -399,14 +459,17 @@ static int launch_cfg(const ConvArgs &a)
     using C = Cfg<KW, KA, PIX, KT, CH, MODE>;
     if (a.pad > kActBorder) return EBS_ERR_UNSUPPORTED;   // taps would leave the stored zero ring
     if (a.cw % CH != 0) return EBS_ERR_UNSUPPORTED;       // chunks are whole: no ragged last chunk
+    if (FS > 0 && (a.R != FS || a.S != FS)) return EBS_ERR_UNSUPPORTED;
     TiledShape sh{};
-    sh.N = a.N; sh.H = a.H; sh.W = a.W; sh.K = a.K; sh.R = a.R; sh.S = a.S;
-    sh.stride = a.stride; sh.pad = a.pad; sh.OH = a.OH; sh.OW = a.OW; sh.cw = a.cw;
+    sh.K = a.K; sh.R = a.R; sh.S = a.S;
+    sh.stride = a.stride; sh.pad = a.pad; sh.OW = a.OW; sh.cw = a.cw;
     sh.Hp = a.H + 2 * kActBorder; sh.Wp = a.W + 2 * kActBorder; sh.RS = a.R * a.S;
     sh.total = a.N * a.OH * a.OW;
-    sh.nchunks = (a.cw + CH - 1) / CH;
+    sh.nchunks = a.cw / CH;
     sh.per_channel = a.per_channel;
     sh.wgroups = (a.K + kWgtGroup - 1) / kWgtGroup;
+    sh.div_ow = make_fastdiv((uint32_t)a.OW);
+    sh.div_ohow = make_fastdiv((uint32_t)(a.OH * a.OW));
 
     TileGeom g{a.H, a.W, a.R, a.S, a.stride, a.pad, a.OH, a.OW, kActBorder};
     long long tp = C::TP < sh.total ? C::TP : sh.total;
@@ -422,48 +485,59 @@ static int launch_cfg(const ConvArgs &a)
 
     long long ptiles = ((long long)sh.total + C::TP - 1) / C::TP;
     long long kblocks = ((long long)a.K + C::KB - 1) / C::KB;
-    if (ptiles > 0x7fffffffLL || kblocks > 65535) return EBS_ERR_UNSUPPORTED;
+    long long nblocks = ptiles * kblocks;
+    if (nblocks > (1LL << 30)) return EBS_ERR_UNSUPPORTED;
+    sh.kblocks = (int)kblocks;
+    sh.nblocks = (int)nblocks;
+    sh.xcd_chunk = (int)((nblocks + 7) / 8);
+    sh.div_kblocks = make_fastdiv((uint32_t)kblocks);
 
-    hipLaunchKernelGGL((bd_conv_tiled<KW, KA, PIX, KT, CH, MODE>), dim3((unsigned)ptiles, (unsigned)kblocks), dim3(256),
+    // A grid that fits the machine in one go is dealt unevenly to the compute units; asking
+    // for more LDS than needed caps the work-groups per unit at ceil(nblocks / units).
+    long long per_cu = (nblocks + kNumCus - 1) / kNumCus;
+    if (per_cu >= 2 && per_cu < 8) {
+        size_t want = kLdsPerCu / (size_t)(per_cu + 1) + 512;
+        if (want > kMaxLdsBytes) want = kMaxLdsBytes;
+        if (want > lds_bytes) lds_bytes = want;
+    }
+
+    hipLaunchKernelGGL((bd_conv_tiled<KW, KA, PIX, KT, CH, MODE, FS>), dim3((unsigned)(sh.xcd_chunk * 8)), dim3(256),
                        lds_bytes, a.stream, a.act, a.wgt, a.scale, a.offset, a.acc, a.out, sh);
     return hip_ok(hipGetLastError());
 }
 
 // Variant table: (index, accumulator budget, words per staged chunk, wave arrangement).
 #define EBS_TILED_VARIANTS(X)                                               \
-    X(0, 128, 2, MODE_P4)  X(1, 128, 1, MODE_P4)  X(2, 128, 4, MODE_P4)     \
-    X(3, 64, 2, MODE_P4)   X(4, 64, 1, MODE_P4)   X(5, 64, 4, MODE_P4)      \
-    X(6, 32, 2, MODE_P4)   X(7, 32, 1, MODE_P4)   X(8, 32, 4, MODE_P4)      \
-    X(9, 128, 2, MODE_K4)  X(10, 128, 1, MODE_K4) X(11, 128, 4, MODE_K4)    \
-    X(12, 64, 2, MODE_K4)  X(13, 64, 1, MODE_K4)  X(14, 64, 4, MODE_K4)     \
-    X(15, 32, 2, MODE_K4)  X(16, 32, 1, MODE_K4)  X(17, 32, 4, MODE_K4)     \
-    X(18, 128, 4, MODE_R4) X(19, 64, 4, MODE_R4)  X(20, 32, 4, MODE_R4)     \
-    X(21, 16, 2, MODE_K4)  X(22, 16, 1, MODE_K4)  X(23, 16, 4, MODE_K4)     \
-    X(24, 16, 4, MODE_R4)
-constexpr int kNumTiledVariants = 25;
+    X(0, 64, 2, MODE_P4)   X(1, 64, 1, MODE_P4)   X(2, 64, 4, MODE_P4)      \
+    X(3, 32, 2, MODE_P4)   X(4, 32, 1, MODE_P4)   X(5, 32, 4, MODE_P4)      \
+    X(6, 64, 2, MODE_K4)   X(7, 64, 1, MODE_K4)   X(8, 64, 4, MODE_K4)      \
+    X(9, 32, 2, MODE_K4)   X(10, 32, 1, MODE_K4)  X(11, 32, 4, MODE_K4)     \
+    X(12, 16, 2, MODE_K4)  X(13, 16, 1, MODE_K4)  X(14, 16, 4, MODE_K4)     \
+    X(15, 64, 4, MODE_R4)  X(16, 32, 4, MODE_R4)  X(17, 16, 4, MODE_R4)
+constexpr int kNumTiledVariants = 18;
 
-template <int KW, int KA>
+template <int KW, int KA, int FS>
 static int launch_bits(const ConvArgs &a, int v)
 {
     switch (v) {
-#define EBS_X(idx, b, ch, mode) case idx: return launch_cfg<KW, KA, b, ch, mode>(a);
+#define EBS_X(idx, b, ch, mode) case idx: return launch_cfg<KW, KA, b, ch, mode, FS>(a);
         EBS_TILED_VARIANTS(EBS_X)
 #undef EBS_X
     }
     return EBS_ERR_UNSUPPORTED;
 }
 
-// One translation unit per weight bitwidth instantiates these.
-template <int KW> int launch_tiled_kw(const ConvArgs &a, int v);
+// One translation unit per (weight bitwidth, filter specialisation) instantiates these.
+template <int KW, int FS> int launch_tiled_kw(const ConvArgs &a, int v);
 
-#define EBS_DEFINE_TILED_KW(KWV)                                            \
-    template <> int launch_tiled_kw<KWV>(const ConvArgs &a, int v)          \
+#define EBS_DEFINE_TILED_KW(KWV, FSV)                                       \
+    template <> int launch_tiled_kw<KWV, FSV>(const ConvArgs &a, int v)     \
     {                                                                       \
         switch (a.ka) {                                                     \
-            case 1: return launch_bits<KWV, 1>(a, v);                       \
-            case 2: return launch_bits<KWV, 2>(a, v);                       \
-            case 3: return launch_bits<KWV, 3>(a, v);                       \
-            case 4: return launch_bits<KWV, 4>(a, v);                       \
+            case 1: return launch_bits<KWV, 1, FSV>(a, v);                  \
+            case 2: return launch_bits<KWV, 2, FSV>(a, v);                  \
+            case 3: return launch_bits<KWV, 3, FSV>(a, v);                  \
+            case 4: return launch_bits<KWV, 4, FSV>(a, v);                  \
         }                                                                   \
         return EBS_ERR_BITWIDTH;                                            \
     }

@@ -1,0 +1,5 @@
+// Tiled convolution kernels: 1-bit weights, 3x3 filter specialisation (all activation bitwidths, all variants).
+#include "conv_tiled_kernel.h"
+namespace ebs {
+EBS_DEFINE_TILED_KW(1, 3)
+}

@@ -1,0 +1,5 @@
+// Tiled convolution kernels: 2-bit weights, generic filter (all activation bitwidths, all variants).
+#include "conv_tiled_kernel.h"
+namespace ebs {
+EBS_DEFINE_TILED_KW(2, 0)
+}
