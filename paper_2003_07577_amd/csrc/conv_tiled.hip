@@ -68,9 +68,13 @@ int launch_conv_tiled(const ConvArgs &a, int variant)
     const int ncls = a.kw + a.ka - 1;
     const int slot = ch_slot(a.cw);
     const int budget = ncls <= 2 ? 16 : 32;
+    const int rs = a.R * a.S;
+    // GEMM-shaped layers with few rows (a fully-connected layer as a 1x1 convolution): the
+    // one-output-per-thread kernel, whose lanes run along the channels, is the faster one.
+    if (rs == 1 && positions <= 4096) return EBS_ERR_UNSUPPORTED;
     int order[6];
     int n = 0;
-    if (positions <= 4096 && a.cw >= 16 && a.cw % 4 == 0) order[n++] = V_R4_32;
+    if (rs > 1 && rs * a.cw >= 64 && positions <= 16384 && a.cw % 4 == 0) order[n++] = V_R4_16;
     if (a.K >= 4 * kt_of(budget, ncls)) order[n++] = (budget == 16 ? V_K4_16 : V_K4_32) + slot;
     else if (a.K >= 4 * kt_of(16, ncls)) order[n++] = V_K4_16 + slot;
     order[n++] = V_P4_32 + slot;
