@@ -97,6 +97,7 @@ struct Cfg {
     static constexpr int KB = WK * KT;               // channels per work-group
     static constexpr int POSW = CH * KAP;            // LDS dwords per staged position (all words of the chunk)
     static constexpr int WSTEP = CH / WRED;          // reduction words per wave per tap per chunk
+    static constexpr int WPS = (NCLS <= 2 && WSTEP % 2 == 0) ? 2 : 1;   // words per pipelined step (3x3 path)
     static constexpr int KG = (KT + kWgtGroup - 1) / kWgtGroup;   // 16-channel weight groups per tile
     static constexpr int KTG = KT < kWgtGroup ? KT : kWgtGroup;   // channels taken from one group
     // output tile of one epilogue pass, [row = position][col = channel], padded pitch
@@ -261,44 +262,59 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
                 for (int i = 0; i < KW; ++i) qc[c][i] = qn[c][i];
         };
 
-        uint32_t xc[PIX][KA], qc[KT][KW];
         int qoff = 0;
-        fetch_q(0, qc);
 
         if constexpr (FS > 0) {
             // ---- fixed FS x FS filter: per filter row one LDS address per (position, word);
-            //      the taps of the row are instruction immediates
+            //      the taps of the row are instruction immediates.  A step covers WPS words:
+            //      two for the low bit products, whose single-word steps are too short to
+            //      cover the operand latency when few waves share a SIMD.
+            constexpr int WPS = C::WPS;
+            constexpr int NGRP = C::WSTEP / WPS;       // steps per tap
+            const int q_wrap_g = (sh.cw - (C::WSTEP - WPS) * C::WRED) * (kWgtGroup * KW);
+            uint32_t xg[WPS][PIX][KA], qg[WPS][KT][KW];
             int addr[PIX][C::WSTEP];
 #pragma unroll
             for (int p = 0; p < PIX; ++p)
 #pragma unroll
                 for (int ws = 0; ws < C::WSTEP; ++ws) addr[p][ws] = my_lds[p] + (ws * C::WRED + wred) * wstride;
 #pragma unroll
-            for (int p = 0; p < PIX; ++p) load_x(addr[p][0], xc[p]);
+            for (int u = 0; u < WPS; ++u) {
+                fetch_q(u * QSTEP, qg[u]);
+#pragma unroll
+                for (int p = 0; p < PIX; ++p) load_x(addr[p][u], xg[u][p]);
+            }
             for (int r = 0; r < FS; ++r) {
                 const bool more_rows = r + 1 < FS;
 #pragma unroll
                 for (int s = 0; s < FS; ++s) {
 #pragma unroll
-                    for (int ws = 0; ws < C::WSTEP; ++ws) {
-                        const bool last_in_row = (s + 1 == FS) && (ws + 1 == C::WSTEP);
-                        const bool wrap = ws + 1 == C::WSTEP;          // next step starts a new tap
+                    for (int g = 0; g < NGRP; ++g) {
+                        const bool wrap = g + 1 == NGRP;               // next step starts a new tap
+                        const bool last_in_row = (s + 1 == FS) && wrap;
                         const bool have_next = !last_in_row || more_rows;
                         // The current operands were requested a whole step ago: wait for them BEFORE
                         // the next requests go out (LDS and scalar loads share one counter that can
                         // only be waited to zero, so a wait placed later would also cover the new ones).
                         __builtin_amdgcn_s_waitcnt(0xC07F);     // lgkmcnt(0) only
-                        uint32_t xn[PIX][KA], qn[KT][KW];
+                        uint32_t xn[WPS][PIX][KA], qn[WPS][KT][KW];
                         if (have_next) {
-                            qoff += wrap ? q_wrap : QSTEP;
-                            fetch_q(qoff, qn);
-                            const int nws = wrap ? 0 : ws + 1;
+                            qoff += wrap ? q_wrap_g : WPS * QSTEP;
+                            const int nws = wrap ? 0 : (g + 1) * WPS;
                             const int noff = last_in_row ? rowstride : (wrap ? (s + 1) * C::KAP : s * C::KAP);
 #pragma unroll
-                            for (int p = 0; p < PIX; ++p) load_x(addr[p][nws] + noff, xn[p]);
+                            for (int u = 0; u < WPS; ++u) {
+                                fetch_q(qoff + u * QSTEP, qn[u]);
+#pragma unroll
+                                for (int p = 0; p < PIX; ++p) load_x(addr[p][nws + u] + noff, xn[u][p]);
+                            }
                         }
-                        mac(xc, qc);
-                        if (have_next) rotate(xc, qc, xn, qn);
+#pragma unroll
+                        for (int u = 0; u < WPS; ++u) mac(xg[u], qg[u]);
+                        if (have_next) {
+#pragma unroll
+                            for (int u = 0; u < WPS; ++u) rotate(xg[u], qg[u], xn[u], qn[u]);
+                        }
                     }
                 }
 #pragma unroll
@@ -311,6 +327,8 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
             const int w_first = wred * wstride;    // LDS dword offset of this wave's first word
             int tap_off = 0;                       // (r*Wp + s) * KAP of the current tap
             int s_col = 0;
+            uint32_t xc[PIX][KA], qc[KT][KW];
+            fetch_q(0, qc);
 #pragma unroll
             for (int p = 0; p < PIX; ++p) load_x(my_lds[p] + w_first, xc[p]);
             for (int tap = 0; tap < RS; ++tap) {
