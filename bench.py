@@ -40,6 +40,10 @@ def parse():
     ap.add_argument("--workload", default="resnet18", choices=sorted(WORKLOADS))
     ap.add_argument("--kernel-reps", type=int, default=10, help="back-to-back launches per case for per-kernel timing")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-mfma", action="store_true", help="skip the int8 matrix-core comparison timing")
+    ap.add_argument("--traffic-pass", action="store_true",
+                    help="no timing: one copy of known size (256 MiB) and one pass of the workload, to be run under "
+                         "`rocprofv3 --pmc FETCH_SIZE` and again under `--pmc WRITE_SIZE`")
     ap.add_argument("--cases-out", default=None, help="write the per-case table (JSON) here")
     ap.add_argument("--variant", type=int, default=0, help="conv kernel variant (0 = library heuristic)")
     return ap.parse_args()
@@ -106,6 +110,19 @@ def pack_bytes(case):
     return L.N * L.H * L.W * L.C + L.N * (L.H + 2) * (L.W + 2) * cw * case.k_a * 4
 
 
+def read_traffic(workload):
+    """HBM bytes per convolution launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two
+    separate runs, scaled by a copy kernel of known size); the committed summary holds the figure."""
+    path = os.path.join(ROOT, "profiles", f"bd_conv_{workload}_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":")[1].split()[0])
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(cases):
     """The oracle as it stands, timed on the host cores: each distinct layer shape once
     (its time does not depend on the bitwidths), aggregated over the cases of the workload."""
@@ -169,6 +186,20 @@ def main():
     for c in cases:
         bufs.append(CaseBuffers(c, wl.make_inputs(c), shared, dev))
     torch.cuda.synchronize()
+
+    if args.traffic_pass:
+        n = 256 << 20
+        src = torch.empty(n, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty(n, dtype=torch.uint8, device=dev)
+        torch.cuda.synchronize()
+        ebs.ebs_probe_copy(src, dst, n, 4096, stream)
+        torch.cuda.synchronize()
+        for b in bufs:
+            b.pack(ebs, stream)
+            b.conv(ebs, stream, args.variant)
+            torch.cuda.synchronize()
+        print(json.dumps({"traffic_pass": True, "copy_bytes": n, "cases": len(bufs)}))
+        return
 
     def step():
         for b in bufs:
@@ -243,6 +274,48 @@ def main():
         "avg_launch_us": round(pack_us_sum / len(bufs), 2),
     }
 
+    # ---- measured comparison: the same layers on the int8 matrix cores (no binary decomposition);
+    #      its time does not depend on the bitwidths, so each layer shape is timed once
+    mfma = None
+    if not args.no_mfma:
+        per_layer = {}
+        for b in bufs:
+            L = b.case.layer
+            if L in per_layer or L.C % 32 != 0:
+                continue
+            import paper_2003_07577_amd as ebs_mod
+            wl_inp = wl.make_inputs(b.case)
+            qd = torch.from_numpy(wl_inp["q"]).to(dev)
+            f = lambda: ebs_mod.ebs_mixed_conv2d_mfma_i8(b.a, qd, L.N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad,
+                                                          b.scale, b.offset, b.per_channel, b.acc, b.out, stream)
+            f()
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+            ev[0].record(stream)
+            for _ in range(args.kernel_reps):
+                f()
+            ev[1].record(stream)
+            torch.cuda.synchronize()
+            per_layer[L] = ev[0].elapsed_time(ev[1]) * 1e3 / args.kernel_reps
+        covered = [b.case for b in bufs if b.case.layer in per_layer]
+        if covered:
+            t_us = sum(per_layer[c.layer] for c in covered)
+            macs = sum(L.int_macs for L in per_layer)
+            mfma = {
+                "kernel": "ebs_mixed_conv2d_mfma_i8 (comparison only, not the default path)",
+                "equivalent_binary_tops": round(sum(c.binary_ops for c in covered) / t_us / 1e6, 1),
+                "int8_tmacs": round(macs / sum(per_layer.values()) / 1e6, 1),
+                "frac_of_int8_mfma_peak": round(2 * macs / sum(per_layer.values()) / 1e6 / 5000.0, 4),
+                "layer_us": {L.name: round(t, 1) for L, t in per_layer.items()},
+            }
+            for r in table:
+                L = [c.layer for c in cases if c.tag == r["case"]][0]
+                if L in per_layer:
+                    r["mfma_i8_us"] = round(per_layer[L], 2)
+
+    traffic = read_traffic(args.workload)
+    if traffic is not None:
+        roofline["traffic"] = traffic
+
     out = {
         "metric": "effective binary TOP/s of mixed-precision conv layers (pack_activations + conv per layer)",
         "value": round(value, 2), "unit": "TOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -254,6 +327,8 @@ def main():
         "wall_s": round(wall, 3),
         "roofline": roofline, "pack_roofline": pack_roof,
     }
+    if mfma is not None:
+        out["mfma_i8_comparison"] = mfma
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cases)
     cases_out = args.cases_out
