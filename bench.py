@@ -41,6 +41,8 @@ def parse():
     ap.add_argument("--kernel-reps", type=int, default=10, help="back-to-back launches per case for per-kernel timing")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-mfma", action="store_true", help="skip the int8 matrix-core comparison timing")
+    ap.add_argument("--only", default=None, metavar="LAYER,KW,KA",
+                    help="restrict the workload to one case (layer index and bitwidths), e.g. 0,2,2")
     ap.add_argument("--traffic-pass", action="store_true",
                     help="no timing: one copy of known size (256 MiB) and one pass of the workload, to be run under "
                          "`rocprofv3 --pmc FETCH_SIZE` and again under `--pmc WRITE_SIZE`")
@@ -180,6 +182,12 @@ def main():
 
     cfg = WORKLOADS[args.workload]
     cases = wl.config_cases(cfg)
+    if args.only:
+        li, kw, ka = (int(v) for v in args.only.split(","))
+        cases = [c for c in cases if (c.layer_index, c.k_w, c.k_a) == (li, kw, ka)]
+        if not cases:
+            print("--only matches no case", file=sys.stderr)
+            sys.exit(1)
     max_out = max(c.layer.N * c.layer.OH * c.layer.OW * c.layer.K for c in cases)
     shared = SharedOutputs(dev, max_out)
     bufs = []
