@@ -234,3 +234,27 @@ def test_mfma_i8_comparison_matches_oracle(oracle_mod):
     # unsupported channel count is an error code, not a crash
     rc = ebs.ebs_mixed_conv2d_mfma_i8(a, q, 1, 16, 4, 4, 8, 3, 3, 1, 1, sc, None, 0, acc, out, None, check=False)
     assert rc == -5
+
+
+# ------------------------------------------------------------------ measurement probes
+def test_probes_run_and_report_plausible_rates():
+    import torch
+    dev = torch.device("cuda:0")
+    seed = torch.randint(0, 2 ** 31 - 1, (512,), dtype=torch.int32, device=dev)
+    blocks, trips = 512, 200
+    sink = torch.zeros(blocks * 256, dtype=torch.int32, device=dev)
+    ebs.ebs_probe_and_bcnt(seed, sink, blocks, trips)
+    torch.cuda.synchronize()
+    assert ebs.ebs_probe_and_bcnt_pairs(blocks, trips) == blocks * 256 * trips * 128
+    assert int(sink.max().item()) > 0                      # the counted bits are observable
+    n = 1 << 24
+    src = torch.arange(n // 4, dtype=torch.int32, device=dev)
+    dst = torch.zeros(n // 4, dtype=torch.int32, device=dev)
+    ebs.ebs_probe_copy(src, dst, n, 256)
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst)
+    ebs.ebs_probe_copy(None, dst, n, 256)                  # fill variant: writes the pattern 1,2,3,4
+    torch.cuda.synchronize()
+    assert dst[:8].tolist() == [1, 2, 3, 4, 1, 2, 3, 4]
+    assert ebs.ebs_probe_copy(src, dst, 7, 256, check=False) == -3
+    assert ebs.ebs_probe_and_bcnt(None, sink, 1, 1, check=False) == -1
