@@ -33,8 +33,8 @@ _lib = None
 def build(force: bool = False) -> str:
     """Compile the C oracle with gcc (host only, OpenMP for the timed baseline)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c99", "-Wall", "-Wextra",
-               "-o", _LIB, _SRC]
+        cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c99", "-ffp-contract=off", "-Wall", "-Wextra",
+               "-o", _LIB, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -56,6 +56,8 @@ def _load():
         lib.oracle_bitplane_conv.restype = ci
         lib.oracle_dequant.argtypes = [i32p, ctypes.c_size_t, ci, f32p, f32p, ci, f32p]
         lib.oracle_dequant.restype = None
+        lib.oracle_requant_levels.argtypes = [i32p, ctypes.c_size_t, ci, f32p, f32p, ci, ctypes.c_float, ci, u8p]
+        lib.oracle_requant_levels.restype = None
         lib.oracle_num_threads.argtypes = []
         lib.oracle_num_threads.restype = ci
         _lib = lib
@@ -149,6 +151,28 @@ def dequant(acc, scale, offset=None, per_channel=False):
     lib.oracle_dequant(acc.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), n_pix, K,
                        scale.ctypes.data_as(f32p), op, 1 if per_channel else 0,
                        out.ctypes.data_as(f32p))
+    return out
+
+
+def requant_levels(acc, scale, offset, per_channel, alpha, bits):
+    """Next layer's activation levels (Eq. 1b-1c, round half up) of x = scale*acc + offset,
+    in the fixed single-precision order documented in bd_oracle.c.  acc is [...][K]."""
+    lib = _load()
+    acc = np.ascontiguousarray(acc, dtype=np.int32)
+    K = acc.shape[-1]
+    scale = np.ascontiguousarray(np.atleast_1d(scale), dtype=np.float32)
+    f32p = ctypes.POINTER(ctypes.c_float)
+    op = None
+    if offset is not None:
+        offset = np.ascontiguousarray(np.atleast_1d(offset), dtype=np.float32)
+        op = offset.ctypes.data_as(f32p)
+    need = K if per_channel else 1
+    if scale.size < need or (offset is not None and offset.size < need):
+        raise ValueError("scale/offset too short")
+    out = np.empty(acc.shape, dtype=np.uint8)
+    lib.oracle_requant_levels(acc.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), acc.size // K, K,
+                              scale.ctypes.data_as(f32p), op, 1 if per_channel else 0,
+                              ctypes.c_float(alpha), bits, out.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)))
     return out
 
 

@@ -33,6 +33,7 @@
 #include <stddef.h>
 #include <stdlib.h>
 #include <string.h>
+#include <math.h>
 
 static int out_extent(int in, int pad, int filt, int stride)
 {
@@ -181,6 +182,32 @@ void oracle_dequant(const int32_t *acc, size_t n_pix, int K,
             double sc = (double)scale[idx];
             double of = offset ? (double)offset[idx] : 0.0;
             out[p * K + k] = (float)(sc * (double)acc[p * K + k] + of);
+        }
+}
+
+/*
+ * Fused re-quantisation: the NEXT layer's activation quantiser (Eq. 1b-1c: clip to
+ * [0, alpha] - which includes the ReLU -, normalise, round half up to b bits) applied to
+ * this layer's affine output x = scale[k]*acc + offset[k].  Returns integer levels.
+ * A rounding decides an integer here, so the precision and the order of operations are
+ * fixed (single precision, the kernel's):
+ *     x  = fmaf((float)acc, scale, offset)
+ *     z  = min(max(x, 0), alpha)
+ *     qs = (float)(2^b - 1) / alpha                       (one IEEE division)
+ *     level = (int) floorf(fmaf(z, qs, 0.5f))             (round half up)
+ */
+void oracle_requant_levels(const int32_t *acc, size_t n_pix, int K,
+                           const float *scale, const float *offset, int per_channel,
+                           float alpha, int bits, uint8_t *levels)
+{
+    const float qs = (float)((1 << bits) - 1) / alpha;
+    for (size_t p = 0; p < n_pix; ++p)
+        for (int k = 0; k < K; ++k) {
+            int idx = per_channel ? k : 0;
+            float of = offset ? offset[idx] : 0.0f;
+            float x = fmaf((float)acc[p * K + k], scale[idx], of);
+            float z = fminf(fmaxf(x, 0.0f), alpha);
+            levels[p * K + k] = (uint8_t)(int)floorf(fmaf(z, qs, 0.5f));
         }
 }
 

@@ -270,3 +270,53 @@ def test_op_count_formula():
     assert c.binary_ops == 2 * s * n * co * 1 * 1
     c44 = [x for x in config_cases(3) if x.layer_index == 0 and (x.k_w, x.k_a) == (4, 4)][0]
     assert c44.binary_ops == 16 * c.binary_ops
+
+
+# ---------------------------------------------------------------- fused re-quantisation (Eq. 1b-1c)
+def test_requant_hand_examples(oracle_mod):
+    import os
+    from golden_io import GOLDEN
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "requant_examples.txt"))
+            if l.strip() and not l.startswith("#") and not l.startswith("[")]
+    assert len(rows) >= 15
+    for bits, alpha, scale, offset, acc, exp in rows:
+        got = oracle_mod.requant_levels(np.array([[int(acc)]], np.int32), np.float32(scale), np.float32(offset),
+                                        False, float(alpha), int(bits))
+        assert int(got[0, 0]) == int(exp), (bits, alpha, scale, offset, acc, exp, int(got[0, 0]))
+
+
+@pytest.mark.parametrize("bits,alpha", [(2, 3.0), (4, 7.5), (3, 3.5), (1, 1.0), (4, 15.0)])
+def test_requant_matches_float64_formula_on_exact_inputs(oracle_mod, bits, alpha):
+    """With (2^b-1)/alpha an integer and power-of-two scales, every intermediate is exact in
+    single precision, so the float64 textbook formula must give the same levels."""
+    acc = np.arange(-50, 400, dtype=np.int32).reshape(-1, 1)
+    for scale, offset in [(0.25, 0.125), (0.5, -3.0), (0.0625, 0.0)]:
+        got = oracle_mod.requant_levels(acc, np.float32(scale), np.float32(offset), False, alpha, bits)
+        x = scale * acc.astype(np.float64) + offset
+        top = 2 ** bits - 1
+        ref = np.floor(top * np.clip(x, 0, alpha) / alpha + 0.5).astype(np.int64)
+        assert np.array_equal(got.astype(np.int64), ref)
+        assert got.max() <= top and got.min() >= 0
+        assert np.all(np.diff(got[:, 0].astype(np.int64)) >= 0)          # monotone for positive scale
+
+
+def test_requant_per_channel_and_general_inputs_close_to_float64(oracle_mod):
+    """Arbitrary scales: the single-precision decision may differ from float64 only where
+    qs*x + 0.5 is within rounding distance of an integer."""
+    rng = np.random.default_rng(5)
+    K = 7
+    acc = rng.integers(-200, 5000, (300, K), dtype=np.int32)
+    sc = rng.uniform(0.001, 0.01, K).astype(np.float32)
+    of = rng.normal(0, 0.5, K).astype(np.float32)
+    alpha, bits = 6.0, 3
+    got = oracle_mod.requant_levels(acc, sc, of, True, alpha, bits).astype(np.int64)
+    x = sc.astype(np.float64) * acc + of.astype(np.float64)
+    y = 7 * np.clip(x, 0, alpha) / alpha + 0.5
+    ref = np.floor(y).astype(np.int64)
+    diff = got != ref
+    assert np.all(np.abs(y[diff] - np.round(y[diff])) < 1e-4)          # only at rounding boundaries
+    assert diff.mean() < 0.01
+    # per-layer call equals per-channel call with constant arrays
+    a = oracle_mod.requant_levels(acc, np.float32(0.004), np.float32(0.1), False, alpha, bits)
+    b = oracle_mod.requant_levels(acc, np.full(K, 0.004, np.float32), np.full(K, 0.1, np.float32), True, alpha, bits)
+    assert np.array_equal(a, b)
