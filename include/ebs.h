@@ -108,6 +108,25 @@ int ebs_mixed_conv2d(const void *packed_act, const void *packed_wgt,
                      int32_t *acc_out, float *out_f32, void *stream);
 
 /*
+ * The same convolution with the NEXT layer's activation quantiser fused into the epilogue
+ * (Eq. 1b-1c: clip to [0, alpha_next] - the clip at 0 is the ReLU -, normalise, round half
+ * up to k_next bits) and the result written directly as the next layer's packed activations:
+ *     x = scale[k]*acc + offset[k];  level = floor((2^k_next - 1)/alpha_next * clip(x, 0, alpha_next) + 0.5)
+ * evaluated in single precision in exactly this order: fmaf(acc, scale, offset), min/max,
+ * fmaf(z, qs, 0.5) with qs = (float)(2^k_next - 1)/alpha_next, floor.  No int32/fp32 tensor is
+ * written (k_next/8 bytes per output instead of 8) and no separate pack call is needed.
+ *   packed_next : out, device, ebs_packed_activations_bytes(N, OH, OW, K, k_next) bytes; ready to
+ *                 be the packed_act of a layer with C = K, H = OH, W = OW (its zero ring is written
+ *                 by this call)
+ * Other arguments as for ebs_mixed_conv2d; alpha_next must be positive and finite.
+ */
+int ebs_mixed_conv2d_requant(const void *packed_act, const void *packed_wgt,
+                             int N, int C, int H, int W, int K, int R, int S,
+                             int stride, int pad, int k_w, int k_a,
+                             const float *scale, const float *offset, int per_channel,
+                             float alpha_next, int k_next, void *packed_next, void *stream);
+
+/*
  * Same call with the kernel variant chosen by the caller instead of the
  * library's shape heuristic; exists so that measurements can sweep tilings.
  * variant 0 = heuristic; ebs_conv_variant_count() gives the number of

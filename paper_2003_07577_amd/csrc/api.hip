@@ -35,7 +35,7 @@ static int check_wgt_shape(int K, int C, int R, int S)
 // Validates a convolution request and fills the geometry fields.
 static int check_conv(ConvArgs &a, const void *p0, const void *p1)
 {
-    if (!p0 || !p1 || !a.scale || !a.acc) return EBS_ERR_NULL;
+    if (!p0 || !p1 || !a.scale || (!a.acc && !a.next)) return EBS_ERR_NULL;
     if (!bits_ok(a.kw) || !bits_ok(a.ka)) return EBS_ERR_BITWIDTH;
     int rc = check_act_shape(a.N, a.H, a.W, a.C);
     if (rc) return rc;
@@ -47,7 +47,8 @@ static int check_conv(ConvArgs &a, const void *p0, const void *p1)
     a.OW = (a.W + 2 * a.pad - a.S) / a.stride + 1;
     a.cw = words_per_pixel(a.C);
     if ((long long)a.N * a.OH * a.OW * a.K > kMaxElems) return EBS_ERR_SHAPE;
-    if (!aligned16(p0) || !aligned16(p1) || !aligned16(a.acc) || (a.out && !aligned16(a.out))) return EBS_ERR_ALIGN;
+    if (!aligned16(p0) || !aligned16(p1) || !aligned16(a.acc) || (a.out && !aligned16(a.out)) || !aligned16(a.next))
+        return EBS_ERR_ALIGN;
     if ((reinterpret_cast<uintptr_t>(a.scale) & 3u) || (a.offset && (reinterpret_cast<uintptr_t>(a.offset) & 3u)))
         return EBS_ERR_ALIGN;
     return EBS_OK;
@@ -170,6 +171,33 @@ int ebs_mixed_conv2d_mfma_i8(const uint8_t *act_levels, const uint8_t *wgt_level
     int rc = check_conv(a, act_levels, wgt_levels);
     if (rc) return rc;
     return launch_conv_mfma_i8(act_levels, wgt_levels, a);
+}
+
+int ebs_mixed_conv2d_requant(const void *packed_act, const void *packed_wgt,
+                             int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                             int k_w, int k_a, const float *scale, const float *offset, int per_channel,
+                             float alpha_next, int k_next, void *packed_next, void *stream)
+{
+    if (!packed_next) return EBS_ERR_NULL;
+    if (!bits_ok(k_next)) return EBS_ERR_BITWIDTH;
+    if (!(alpha_next > 0.0f) || !(alpha_next < 3.0e38f)) return EBS_ERR_SHAPE;
+    ConvArgs a{};
+    a.act = (const uint32_t *)packed_act;
+    a.wgt = (const uint32_t *)packed_wgt;
+    a.N = N; a.C = C; a.H = H; a.W = W; a.K = K; a.R = R; a.S = S;
+    a.stride = stride; a.pad = pad; a.kw = k_w; a.ka = k_a;
+    a.scale = scale; a.offset = offset; a.per_channel = per_channel ? 1 : 0;
+    a.next = (uint32_t *)packed_next; a.alpha = alpha_next; a.k_next = k_next;
+    a.stream = (hipStream_t)stream;
+    int rc = check_conv(a, packed_act, packed_wgt);
+    if (rc) return rc;
+    rc = check_act_shape(N, a.OH, a.OW, K);          // the next layer's packed tensor must be addressable
+    if (rc) return rc;
+    rc = launch_zero_border(a.next, N, a.OH, a.OW, words_per_pixel(K) * k_next, a.stream);
+    if (rc) return rc;
+    rc = launch_requant_tiled(a);
+    if (rc == EBS_ERR_UNSUPPORTED) rc = launch_requant_naive(a);
+    return rc;
 }
 
 int ebs_check_levels(const uint8_t *levels, size_t count, int bits, int32_t *device_flag, void *stream)

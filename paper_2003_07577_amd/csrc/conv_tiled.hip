@@ -5,9 +5,12 @@
 namespace ebs {
 
 template <int KW, int FS> int launch_tiled_kw(const ConvArgs &a, int v);
+template <int KW, int FS> int launch_tiled_req_kw(const ConvArgs &a, int v);
 #define EBS_DECL(kw) \
     template <> int launch_tiled_kw<kw, 0>(const ConvArgs &a, int v); \
-    template <> int launch_tiled_kw<kw, 3>(const ConvArgs &a, int v);
+    template <> int launch_tiled_kw<kw, 3>(const ConvArgs &a, int v); \
+    template <> int launch_tiled_req_kw<kw, 0>(const ConvArgs &a, int v); \
+    template <> int launch_tiled_req_kw<kw, 3>(const ConvArgs &a, int v);
 EBS_DECL(1) EBS_DECL(2) EBS_DECL(3) EBS_DECL(4)
 #undef EBS_DECL
 
@@ -45,6 +48,18 @@ static int run_variant(const ConvArgs &a, int v)
     return run_fs<0>(a, v);
 }
 
+template <int FS>
+static int run_req_fs(const ConvArgs &a, int v)
+{
+    switch (a.kw) {
+        case 1: return launch_tiled_req_kw<1, FS>(a, v);
+        case 2: return launch_tiled_req_kw<2, FS>(a, v);
+        case 3: return launch_tiled_req_kw<3, FS>(a, v);
+        case 4: return launch_tiled_req_kw<4, FS>(a, v);
+    }
+    return EBS_ERR_BITWIDTH;
+}
+
 // Slot of the chunk size inside a family of three: order ch2, ch1, ch4.
 static int ch_slot(int cw) { return cw % 4 == 0 ? 2 : (cw % 2 == 0 ? 0 : 1); }
 
@@ -54,6 +69,17 @@ static int kt_of(int budget, int ncls)
     static const int k64[7] = {16, 8, 8, 8, 4, 4, 4}, k32[7] = {16, 8, 8, 8, 4, 4, 4}, k16[7] = {16, 8, 4, 4, 4, 4, 4};
     const int *t = budget == 64 ? k64 : budget == 32 ? k32 : k16;
     return t[ncls - 1];
+}
+
+// Fused re-quantisation: the K4 kernels whose work-groups own whole 32-channel words.
+int launch_requant_tiled(const ConvArgs &a)
+{
+    const int order[2] = {ch_slot(a.cw), 1};       // preferred chunk size, then the smallest footprint
+    for (int i = 0; i < 2; ++i) {
+        int rc = (a.R == 3 && a.S == 3) ? run_req_fs<3>(a, order[i]) : run_req_fs<0>(a, order[i]);
+        if (rc != EBS_ERR_UNSUPPORTED) return rc;
+    }
+    return EBS_ERR_UNSUPPORTED;
 }
 
 int launch_conv_tiled(const ConvArgs &a, int variant)

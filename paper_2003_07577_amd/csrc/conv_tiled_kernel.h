@@ -36,6 +36,7 @@
 #pragma once
 #include "ebs_internal.h"
 #include "fastdiv.h"
+#include "requant.h"
 #include "tile_geometry.h"
 #include <cstdlib>
 
@@ -63,6 +64,9 @@ struct TiledShape {
     int nblocks;      // position tiles * channel blocks
     int xcd_chunk;    // ceil(nblocks / 8): logical blocks handled by one die
     FastDiv div_ow, div_ohow, div_kblocks;
+    // fused re-quantisation (REQ kernels only): next layer's quantiser and packed layout
+    float alpha, qs;
+    int k_next, OHn, OWn, cwn;     // bordered output grid (OH+2, OW+2), words per position of the next layer
     int dbg;          // experiment switches; only read in EBS_EXPERIMENT builds
 };
 
@@ -110,11 +114,12 @@ struct Cfg {
     static_assert(256 % (OCOLS / 4) == 0, "write-back assumes a fixed column group per thread");
 };
 
-template <int KW, int KA, int PIX, int KT, int CH, int MODE, int FS>
+template <int KW, int KA, int PIX, int KT, int CH, int MODE, int FS, bool REQ>
 __global__ void __launch_bounds__(256)
 bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
               const float *__restrict__ scale, const float *__restrict__ offset,
-              int32_t *__restrict__ acc_out, float *__restrict__ out_f32, const TiledShape sh)
+              int32_t *__restrict__ acc_out, float *__restrict__ out_f32, uint32_t *__restrict__ packed_next,
+              const TiledShape sh)
 {
     using C = Cfg<KW, KA, PIX, KT, CH, MODE>;
     extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
@@ -417,6 +422,39 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
         __syncthreads();
         if (EBS_DBG(1)) continue;
         // rows of this pass: row r of sub-tile w is position t_first + w*TPW + p*64 + r
+        if constexpr (REQ) {
+            // ---- fused re-quantisation (Eq. 1b-1c) and bit-plane packing for the next layer: the 8
+            //      threads that hold the 32 channels of one word OR their 4-bit pieces together
+            static_assert(!REQ || (CG % 8 == 0), "a packed word needs all 32 channels in one work-group");
+#pragma unroll
+            for (int r0 = 0; r0 < C::OROWS; r0 += RSTEP) {
+                const int row = r0 + tid / CG;
+                const int t = t_first + (row >> 6) * C::TPW + p * 64 + (row & 63);
+                const bool valid = row < C::OROWS && t < sh.total;
+                const int rr = row < C::OROWS ? row : 0;
+                const i32x4 v = *reinterpret_cast<const i32x4 *>(otile + rr * C::OPITCH + cg * 4);
+                uint32_t lv[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    lv[e] = kq + e < sh.K ? requant_level(v[e], sc[e], of[e], sh.alpha, sh.qs) : 0u;
+                const int tc = valid ? t : t_first;
+                const int n = (int)fd_div((uint32_t)tc, sh.div_ohow);
+                const int rem = tc - n * (int)sh.div_ohow.d;
+                const int oh = (int)fd_div((uint32_t)rem, sh.div_ow);
+                const int ow = rem - oh * sh.OW;
+                const size_t pos = ((size_t)n * sh.OHn + oh + kActBorder) * sh.OWn + ow + kActBorder;
+                const int word = kq >> 5;
+                uint32_t *dst = packed_next + (pos * sh.cwn + word) * sh.k_next;
+                for (int j = 0; j < sh.k_next; ++j) {
+                    uint32_t w = (((lv[0] >> j) & 1u) | (((lv[1] >> j) & 1u) << 1) | (((lv[2] >> j) & 1u) << 2) |
+                                  (((lv[3] >> j) & 1u) << 3)) << (4 * (cg & 7));
+                    w |= (uint32_t)__shfl_xor((int)w, 1);
+                    w |= (uint32_t)__shfl_xor((int)w, 2);
+                    w |= (uint32_t)__shfl_xor((int)w, 4);
+                    if (valid && (cg & 7) == 0 && word < sh.cwn) dst[j] = w;
+                }
+            }
+        } else {
 #pragma unroll
         for (int r0 = 0; r0 < C::OROWS; r0 += RSTEP) {
             const int row = r0 + tid / CG;
@@ -442,6 +480,7 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
                 }
             }
         }
+        }
     }
 #ifdef EBS_EXPERIMENT
     if (EBS_DBG(8) && out_f32 && tid == 0) {
@@ -463,13 +502,17 @@ EBS_TILE(32, 1, 2, 16)  EBS_TILE(32, 2, 2, 8)   EBS_TILE(32, 3, 1, 8)  EBS_TILE(
 EBS_TILE(32, 5, 1, 4)   EBS_TILE(32, 6, 1, 4)   EBS_TILE(32, 7, 1, 4)
 EBS_TILE(16, 1, 1, 16)  EBS_TILE(16, 2, 1, 8)   EBS_TILE(16, 3, 1, 4)  EBS_TILE(16, 4, 1, 4)
 EBS_TILE(16, 5, 1, 4)   EBS_TILE(16, 6, 1, 4)   EBS_TILE(16, 7, 1, 4)
+// budget 8: tiles of the re-quantising kernels (>= 8 channels per wave, so that the four waves of a
+// work-group hold whole 32-channel words of the next layer's packed activations)
+EBS_TILE(8, 1, 1, 16)   EBS_TILE(8, 2, 1, 8)    EBS_TILE(8, 3, 1, 8)   EBS_TILE(8, 4, 1, 8)
+EBS_TILE(8, 5, 1, 8)    EBS_TILE(8, 6, 1, 8)    EBS_TILE(8, 7, 1, 8)
 #undef EBS_TILE
 
 static constexpr size_t kMaxLdsBytes = 64 * 1024;       // per work-group (dynamic LDS without opt-in)
 static constexpr size_t kLdsPerCu = 160 * 1024;         // gfx950
 static constexpr int kNumCus = 256;
 
-template <int KW, int KA, int BUDGET, int CH, int MODE, int FS>
+template <int KW, int KA, int BUDGET, int CH, int MODE, int FS, bool REQ = false>
 static int launch_cfg(const ConvArgs &a)
 {
     constexpr int PIX = TileOf<BUDGET, KW + KA - 1>::PIX;
@@ -488,6 +531,14 @@ static int launch_cfg(const ConvArgs &a)
     sh.wgroups = (a.K + kWgtGroup - 1) / kWgtGroup;
     sh.div_ow = make_fastdiv((uint32_t)a.OW);
     sh.div_ohow = make_fastdiv((uint32_t)(a.OH * a.OW));
+    if (REQ) {
+        sh.alpha = a.alpha;
+        sh.k_next = a.k_next;
+        sh.qs = requant_qs(a.alpha, a.k_next);
+        sh.OHn = a.OH + 2 * kActBorder;
+        sh.OWn = a.OW + 2 * kActBorder;
+        sh.cwn = words_per_pixel(a.K);
+    }
 
     TileGeom g{a.H, a.W, a.R, a.S, a.stride, a.pad, a.OH, a.OW, kActBorder};
     long long tp = C::TP < sh.total ? C::TP : sh.total;
@@ -519,8 +570,8 @@ static int launch_cfg(const ConvArgs &a)
         if (want > lds_bytes) lds_bytes = want;
     }
 
-    hipLaunchKernelGGL((bd_conv_tiled<KW, KA, PIX, KT, CH, MODE, FS>), dim3((unsigned)(sh.xcd_chunk * 8)), dim3(256),
-                       lds_bytes, a.stream, a.act, a.wgt, a.scale, a.offset, a.acc, a.out, sh);
+    hipLaunchKernelGGL((bd_conv_tiled<KW, KA, PIX, KT, CH, MODE, FS, REQ>), dim3((unsigned)(sh.xcd_chunk * 8)), dim3(256),
+                       lds_bytes, a.stream, a.act, a.wgt, a.scale, a.offset, a.acc, a.out, a.next, sh);
     return hip_ok(hipGetLastError());
 }
 
@@ -545,8 +596,21 @@ static int launch_bits(const ConvArgs &a, int v)
     return EBS_ERR_UNSUPPORTED;
 }
 
+// Re-quantising kernels: K4 arrangement, chunk sizes 2 / 1 / 4 (variant 0 / 1 / 2).
+template <int KW, int KA, int FS>
+static int launch_bits_req(const ConvArgs &a, int v)
+{
+    switch (v) {
+        case 0: return launch_cfg<KW, KA, 8, 2, MODE_K4, FS, true>(a);
+        case 1: return launch_cfg<KW, KA, 8, 1, MODE_K4, FS, true>(a);
+        case 2: return launch_cfg<KW, KA, 8, 4, MODE_K4, FS, true>(a);
+    }
+    return EBS_ERR_UNSUPPORTED;
+}
+
 // One translation unit per (weight bitwidth, filter specialisation) instantiates these.
 template <int KW, int FS> int launch_tiled_kw(const ConvArgs &a, int v);
+template <int KW, int FS> int launch_tiled_req_kw(const ConvArgs &a, int v);
 
 #define EBS_DEFINE_TILED_KW(KWV, FSV)                                       \
     template <> int launch_tiled_kw<KWV, FSV>(const ConvArgs &a, int v)     \
@@ -556,6 +620,16 @@ template <int KW, int FS> int launch_tiled_kw(const ConvArgs &a, int v);
             case 2: return launch_bits<KWV, 2, FSV>(a, v);                  \
             case 3: return launch_bits<KWV, 3, FSV>(a, v);                  \
             case 4: return launch_bits<KWV, 4, FSV>(a, v);                  \
+        }                                                                   \
+        return EBS_ERR_BITWIDTH;                                            \
+    }                                                                       \
+    template <> int launch_tiled_req_kw<KWV, FSV>(const ConvArgs &a, int v) \
+    {                                                                       \
+        switch (a.ka) {                                                     \
+            case 1: return launch_bits_req<KWV, 1, FSV>(a, v);              \
+            case 2: return launch_bits_req<KWV, 2, FSV>(a, v);              \
+            case 3: return launch_bits_req<KWV, 3, FSV>(a, v);              \
+            case 4: return launch_bits_req<KWV, 4, FSV>(a, v);              \
         }                                                                   \
         return EBS_ERR_BITWIDTH;                                            \
     }

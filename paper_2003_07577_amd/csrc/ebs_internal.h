@@ -21,6 +21,11 @@ struct ConvArgs {
     int32_t *acc;          // [N*OH*OW][K]
     float *out;            // may be null
     hipStream_t stream;
+    // fused re-quantisation (next != null): instead of acc/out the kernel writes the NEXT layer's
+    // packed activations [N][OH+2][OW+2][ceil(K/32)][k_next]; the zero ring is written first
+    uint32_t *next;
+    float alpha;           // clip of the next layer's activation quantiser
+    int k_next;            // its bitwidth
 };
 
 inline int words_per_pixel(int C) { return (C + 31) / 32; }
@@ -34,8 +39,11 @@ constexpr int kActBorder = 1;
 constexpr int kActTailDwords = 4;
 
 int launch_conv_naive(const ConvArgs &a);
+int launch_requant_naive(const ConvArgs &a);
+int launch_zero_border(uint32_t *packed, int N, int H, int W, int words_per_pos, hipStream_t st);
 // Returns EBS_ERR_UNSUPPORTED when the tiling cannot run this shape.
 int launch_conv_tiled(const ConvArgs &a, int variant);
+int launch_requant_tiled(const ConvArgs &a);
 int conv_tiled_variant_count();
 const char *conv_tiled_variant_name(int variant);
 

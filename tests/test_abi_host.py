@@ -117,3 +117,21 @@ def test_mfma_argument_errors(lib):
     rc = ebs.ebs_mixed_conv2d_mfma_i8(FAKE, FAKE, 1, 16, 8, 8, 16, 3, 3, 1, 5, FAKE, None, 0, FAKE, FAKE, None,
                                       check=False)
     assert rc == -3
+
+
+def test_requant_argument_errors(lib):
+    def call(**kw):
+        d = dict(pa=FAKE, pw=FAKE, N=1, C=16, H=8, W=8, K=16, R=3, S=3, stride=1, pad=1, kw=2, ka=2, sc=FAKE,
+                 of=None, pc=0, alpha=6.0, kn=2, nxt=FAKE)
+        d.update(kw)
+        return ebs.ebs_mixed_conv2d_requant(d["pa"], d["pw"], d["N"], d["C"], d["H"], d["W"], d["K"], d["R"], d["S"],
+                                            d["stride"], d["pad"], d["kw"], d["ka"], d["sc"], d["of"], d["pc"],
+                                            d["alpha"], d["kn"], d["nxt"], None, check=False)
+    assert call(nxt=None) == -1
+    assert call(pa=None) == -1
+    assert call(kn=0) == -2 and call(kn=5) == -2
+    assert call(kw=7) == -2
+    assert call(alpha=0.0) == -3 and call(alpha=-1.0) == -3 and call(alpha=float("inf")) == -3
+    assert call(alpha=float("nan")) == -3
+    assert call(H=0) == -3
+    assert call(nxt=FAKE + 8) == -4
