@@ -41,6 +41,7 @@ def parse():
     ap.add_argument("--kernel-reps", type=int, default=10, help="back-to-back launches per case for per-kernel timing")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-mfma", action="store_true", help="skip the int8 matrix-core comparison timing")
+    ap.add_argument("--no-requant", action="store_true", help="skip timing the fused re-quantising call")
     ap.add_argument("--only", default=None, metavar="LAYER,KW,KA",
                     help="restrict the workload to one case (layer index and bitwidths), e.g. 0,2,2")
     ap.add_argument("--traffic-pass", action="store_true",
@@ -320,6 +321,33 @@ def main():
                 if L in per_layer:
                     r["mfma_i8_us"] = round(per_layer[L], 2)
 
+    # ---- NEXT row: fused re-quantise + re-pack epilogue (replaces conv's 8 B/output and the next pack call)
+    requant = None
+    if not args.no_requant:
+        t_us = 0.0
+        for b, r in zip(bufs, table):
+            c, L = b.case, b.case.layer
+            kn = c.k_a
+            nxt = torch.empty(ebs.ebs_packed_activations_bytes(L.N, L.OH, L.OW, L.K, kn) // 4, dtype=torch.int32, device=dev)
+            f = lambda: ebs.ebs_mixed_conv2d_requant(b.pa, b.pw, L.N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad,
+                                                      c.k_w, c.k_a, b.scale, b.offset, b.per_channel, 6.0, kn, nxt, stream)
+            f()
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+            ev[0].record(stream)
+            for _ in range(5):
+                f()
+            ev[1].record(stream)
+            torch.cuda.synchronize()
+            us = ev[0].elapsed_time(ev[1]) * 1e3 / 5
+            r["requant_us"] = round(us, 2)
+            t_us += us
+            del nxt
+        requant = {
+            "kernel": "ebs_mixed_conv2d_requant (conv + next layer's quantiser + bit-plane packing, incl. zero-ring kernel)",
+            "binary_tops": round(conv_ops / t_us / 1e6, 1), "frac_of_alu_roof": round(conv_ops / t_us / 1e6 / PEAK_BINARY_TOPS, 4),
+            "vs_pack_plus_conv": round((conv_us_sum + pack_us_sum) / t_us, 3),
+        }
+
     traffic = read_traffic(args.workload)
     if traffic is not None:
         roofline["traffic"] = traffic
@@ -337,6 +365,8 @@ def main():
     }
     if mfma is not None:
         out["mfma_i8_comparison"] = mfma
+    if requant is not None:
+        out["requant_epilogue"] = requant
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cases)
     cases_out = args.cases_out
