@@ -50,6 +50,8 @@ def _load():
         ci = ctypes.c_int
         lib.oracle_conv2d_levels.argtypes = [u8p, u8p] + [ci] * 9 + [i32p]
         lib.oracle_conv2d_levels.restype = ci
+        lib.oracle_conv2d_signed_levels.argtypes = [u8p, u8p] + [ci] * 10 + [i32p]
+        lib.oracle_conv2d_signed_levels.restype = ci
         lib.oracle_conv2d_point.argtypes = [u8p, u8p] + [ci] * 13 + [ctypes.POINTER(ctypes.c_int64)]
         lib.oracle_conv2d_point.restype = ci
         lib.oracle_bitplane_conv.argtypes = [u8p, u8p] + [ci] * 11 + [i32p, i32p]
@@ -96,6 +98,21 @@ def conv2d_levels(a_nhwc, q_krsc, stride=1, pad=0):
                                   acc.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)))
     if rc != 0:
         raise RuntimeError(f"oracle_conv2d_levels failed: {rc}")
+    return acc
+
+
+def conv2d_signed_levels(a_nhwc, q_krsc, k_w, stride=1, pad=0):
+    """Direct convolution with the signed integer weights 2q - (2^k_w - 1) of Eq. 1a -> int32 NHWC."""
+    lib = _load()
+    a, ap = _u8(a_nhwc)
+    q, qp = _u8(q_krsc)
+    N, C, H, W, K, R, S = _shapes(a, q)
+    OH, OW = out_dims(H, W, R, S, stride, pad)
+    acc = np.empty((N, OH, OW, K), dtype=np.int32)
+    rc = lib.oracle_conv2d_signed_levels(ap, qp, N, C, H, W, K, R, S, stride, pad, k_w,
+                                         acc.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)))
+    if rc != 0:
+        raise RuntimeError(f"oracle_conv2d_signed_levels failed: {rc}")
     return acc
 
 

@@ -97,6 +97,47 @@ int oracle_conv2d_levels(const uint8_t *a, const uint8_t *q,
     return overflow ? -2 : 0;
 }
 
+/*
+ * Signed-weight form.  The weight quantiser (Eq. 1a) maps an M-bit level q to the real weight
+ * 2*q/(2^M - 1) - 1 = (2q - (2^M - 1)) / (2^M - 1), i.e. the integer weight 2q - (2^M - 1) in
+ * {-(2^M-1), ..., +(2^M-1)} times a scale that is folded into scale[k].  This is the direct
+ * convolution with those integer weights:
+ *     acc_s[n,k,oh,ow] = sum_{c,r,s} (2*q[k,r,s,c] - (2^M - 1)) * a_pad[...]
+ * (for M = 1 the weights are -1/+1).  Returns 0, -1 on bad geometry, -2 on int32 overflow.
+ */
+int oracle_conv2d_signed_levels(const uint8_t *a, const uint8_t *q,
+                                int N, int C, int H, int W, int K, int R, int S,
+                                int stride, int pad, int M, int32_t *acc)
+{
+    int OH, OW;
+    if (N <= 0 || C <= 0 || K <= 0 || R <= 0 || S <= 0 || pad < 0 || M < 1 || M > 8) return -1;
+    if (oracle_out_dims(H, W, R, S, stride, pad, &OH, &OW)) return -1;
+    const int top = (1 << M) - 1;
+    int overflow = 0;
+#pragma omp parallel for collapse(2) schedule(static) reduction(|:overflow)
+    for (int n = 0; n < N; ++n)
+        for (int oh = 0; oh < OH; ++oh)
+            for (int ow = 0; ow < OW; ++ow)
+                for (int k = 0; k < K; ++k) {
+                    int64_t sum = 0;
+                    for (int r = 0; r < R; ++r) {
+                        int h = oh * stride + r - pad;
+                        if (h < 0 || h >= H) continue;          /* zero padding: activation 0 */
+                        for (int s = 0; s < S; ++s) {
+                            int w = ow * stride + s - pad;
+                            if (w < 0 || w >= W) continue;
+                            const uint8_t *ap = a + (((size_t)n * H + h) * W + w) * C;
+                            const uint8_t *qp = q + (((size_t)k * R + r) * S + s) * C;
+                            for (int c = 0; c < C; ++c)
+                                sum += (int64_t)(2 * (int)qp[c] - top) * (int64_t)ap[c];
+                        }
+                    }
+                    if (sum > INT32_MAX || sum < INT32_MIN) overflow = 1;
+                    acc[(((size_t)n * OH + oh) * OW + ow) * K + k] = (int32_t)sum;
+                }
+    return overflow ? -2 : 0;
+}
+
 /* A single output value (for sampled checks at sizes too big to run whole). */
 int oracle_conv2d_point(const uint8_t *a, const uint8_t *q,
                         int N, int C, int H, int W, int K, int R, int S,

@@ -320,3 +320,37 @@ def test_requant_per_channel_and_general_inputs_close_to_float64(oracle_mod):
     a = oracle_mod.requant_levels(acc, np.float32(0.004), np.float32(0.1), False, alpha, bits)
     b = oracle_mod.requant_levels(acc, np.full(K, 0.004, np.float32), np.full(K, 0.1, np.float32), True, alpha, bits)
     assert np.array_equal(a, b)
+
+
+# ---------------------------------------------------------------- signed weights (Eq. 1a)
+@pytest.mark.parametrize("kw,ka", [(1, 1), (1, 4), (2, 2), (3, 2), (4, 4)])
+def test_signed_conv_against_library_and_identity(oracle_mod, kw, ka):
+    N, C, H, W, K, R, S, st, pad = 2, 21, 7, 6, 5, 3, 3, 2, 1
+    a, q = _rand(300 + kw * 4 + ka, N, C, H, W, K, R, S, kw, ka)
+    top = 2 ** kw - 1
+    got = oracle_mod.conv2d_signed_levels(a, q, kw, st, pad)
+    # float64 library convolution with the integer weights 2q - top (exact)
+    wq = 2.0 * q.astype(np.float64) - top
+    ref = torch.nn.functional.conv2d(torch.from_numpy(a.astype(np.float64)).permute(0, 3, 1, 2),
+                                     torch.from_numpy(wq).permute(0, 3, 1, 2), stride=st, padding=pad)
+    assert np.array_equal(got.astype(np.float64), ref.permute(0, 2, 3, 1).numpy())
+    # identity: 2 * (unsigned product) - top * (window sum of the activations)
+    ones = np.ones_like(q)
+    wsum = oracle_mod.conv2d_levels(a, ones, st, pad)
+    uns = oracle_mod.conv2d_levels(a, q, st, pad)
+    assert np.array_equal(got.astype(np.int64), 2 * uns.astype(np.int64) - top * wsum.astype(np.int64))
+
+
+def test_signed_conv_closed_forms(oracle_mod):
+    C, K = 9, 2
+    a = np.full((1, 5, 5, C), 3, np.uint8)
+    # all weights at the top level -> integer weight +top; at level 0 -> -top; 1-bit -> -1/+1
+    for kw in (1, 2, 4):
+        top = 2 ** kw - 1
+        hi = oracle_mod.conv2d_signed_levels(a, np.full((K, 3, 3, C), top, np.uint8), kw, 1, 0)
+        lo = oracle_mod.conv2d_signed_levels(a, np.zeros((K, 3, 3, C), np.uint8), kw, 1, 0)
+        assert np.all(hi == top * 3 * 9 * C) and np.all(lo == -top * 3 * 9 * C)
+    q = np.zeros((1, 1, 1, 2), np.uint8)
+    q[0, 0, 0, 1] = 1                      # weights (-1, +1)
+    a2 = np.array([5, 2], np.uint8).reshape(1, 1, 1, 2)
+    assert oracle_mod.conv2d_signed_levels(a2, q, 1, 1, 0)[0, 0, 0, 0] == -5 + 2
