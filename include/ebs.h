@@ -118,13 +118,31 @@ int ebs_mixed_conv2d(const void *packed_act, const void *packed_wgt,
  *   packed_next : out, device, ebs_packed_activations_bytes(N, OH, OW, K, k_next) bytes; ready to
  *                 be the packed_act of a layer with C = K, H = OH, W = OW (its zero ring is written
  *                 by this call)
+ * signed_weights != 0 selects the signed-weight product of ebs_mixed_conv2d_signed for acc.
  * Other arguments as for ebs_mixed_conv2d; alpha_next must be positive and finite.
  */
 int ebs_mixed_conv2d_requant(const void *packed_act, const void *packed_wgt,
                              int N, int C, int H, int W, int K, int R, int S,
-                             int stride, int pad, int k_w, int k_a,
+                             int stride, int pad, int k_w, int k_a, int signed_weights,
                              const float *scale, const float *offset, int per_channel,
                              float alpha_next, int k_next, void *packed_next, void *stream);
+
+/*
+ * Signed-weight form of ebs_mixed_conv2d.  The weight quantiser (Eq. 1a) maps a level q to the
+ * real weight 2q/(2^k_w - 1) - 1, i.e. to the integer weight 2q - (2^k_w - 1) times a factor the
+ * caller folds into scale[k].  Binary decomposition (Eq. 2, Sec. 4.3) runs on the unsigned levels;
+ * this call adds the data-dependent correction so that
+ *     acc_out = sum (2q - (2^k_w - 1)) * a = 2 * sum q*a - (2^k_w - 1) * sum a
+ * (sum a = window sum of the activation levels, obtained in the same pass from bitcounts of the
+ * activation planes alone), and out_f32 = scale[k]*acc_out + offset[k].  For k_w = 1 the weights
+ * are -1 / +1.  Same packed operands, arguments and conventions as ebs_mixed_conv2d;
+ * ebs_mixed_conv2d_requant takes the same choice through its signed_weights flag.
+ */
+int ebs_mixed_conv2d_signed(const void *packed_act, const void *packed_wgt,
+                            int N, int C, int H, int W, int K, int R, int S,
+                            int stride, int pad, int k_w, int k_a,
+                            const float *scale, const float *offset, int per_channel,
+                            int32_t *acc_out, float *out_f32, void *stream);
 
 /*
  * Same call with the kernel variant chosen by the caller instead of the

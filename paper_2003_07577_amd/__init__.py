@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     ebs_mixed_conv2d,
     ebs_mixed_conv2d_mfma_i8,
     ebs_mixed_conv2d_requant,
+    ebs_mixed_conv2d_signed,
     ebs_mixed_conv2d_variant,
     ebs_pack_activations,
     ebs_pack_weights,

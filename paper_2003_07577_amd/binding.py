@@ -53,7 +53,9 @@ def load_library():
         lib.ebs_mixed_conv2d_variant.restype = _ci
         lib.ebs_mixed_conv2d_variant.argtypes = [_ci] + conv_tail
         lib.ebs_mixed_conv2d_requant.restype = _ci
-        lib.ebs_mixed_conv2d_requant.argtypes = [_vp, _vp] + [_ci] * 11 + [_vp, _vp, _ci, ctypes.c_float, _ci, _vp, _vp]
+        lib.ebs_mixed_conv2d_requant.argtypes = [_vp, _vp] + [_ci] * 12 + [_vp, _vp, _ci, ctypes.c_float, _ci, _vp, _vp]
+        lib.ebs_mixed_conv2d_signed.restype = _ci
+        lib.ebs_mixed_conv2d_signed.argtypes = conv_tail
         lib.ebs_conv_variant_count.restype = _ci
         lib.ebs_conv_variant_name.restype = ctypes.c_char_p
         lib.ebs_conv_variant_name.argtypes = [_ci]
@@ -137,10 +139,21 @@ def ebs_mixed_conv2d(packed_act, packed_wgt, N, C, H, W, K, R, S, stride, pad, k
     return rc
 
 
-def ebs_mixed_conv2d_requant(packed_act, packed_wgt, N, C, H, W, K, R, S, stride, pad, k_w, k_a,
-                             scale, offset, per_channel, alpha_next, k_next, packed_next, stream=None, check=True) -> int:
-    rc = load_library().ebs_mixed_conv2d_requant(
+def ebs_mixed_conv2d_signed(packed_act, packed_wgt, N, C, H, W, K, R, S, stride, pad, k_w, k_a,
+                            scale, offset, per_channel, acc_out, out_f32, stream=None, check=True) -> int:
+    rc = load_library().ebs_mixed_conv2d_signed(
         _ptr(packed_act), _ptr(packed_wgt), N, C, H, W, K, R, S, stride, pad, k_w, k_a,
+        _ptr(scale), _ptr(offset), int(bool(per_channel)), _ptr(acc_out), _ptr(out_f32), _stream(stream))
+    if check:
+        _check(rc, "ebs_mixed_conv2d_signed")
+    return rc
+
+
+def ebs_mixed_conv2d_requant(packed_act, packed_wgt, N, C, H, W, K, R, S, stride, pad, k_w, k_a,
+                             scale, offset, per_channel, alpha_next, k_next, packed_next, stream=None, check=True,
+                             signed_weights=False) -> int:
+    rc = load_library().ebs_mixed_conv2d_requant(
+        _ptr(packed_act), _ptr(packed_wgt), N, C, H, W, K, R, S, stride, pad, k_w, k_a, int(bool(signed_weights)),
         _ptr(scale), _ptr(offset), int(bool(per_channel)), ctypes.c_float(alpha_next), k_next, _ptr(packed_next),
         _stream(stream))
     if check:

@@ -173,9 +173,28 @@ int ebs_mixed_conv2d_mfma_i8(const uint8_t *act_levels, const uint8_t *wgt_level
     return launch_conv_mfma_i8(act_levels, wgt_levels, a);
 }
 
+int ebs_mixed_conv2d_signed(const void *packed_act, const void *packed_wgt,
+                            int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                            int k_w, int k_a, const float *scale, const float *offset, int per_channel,
+                            int32_t *acc_out, float *out_f32, void *stream)
+{
+    ConvArgs a{};
+    a.act = (const uint32_t *)packed_act;
+    a.wgt = (const uint32_t *)packed_wgt;
+    a.N = N; a.C = C; a.H = H; a.W = W; a.K = K; a.R = R; a.S = S;
+    a.stride = stride; a.pad = pad; a.kw = k_w; a.ka = k_a;
+    a.scale = scale; a.offset = offset; a.per_channel = per_channel ? 1 : 0;
+    a.acc = acc_out; a.out = out_f32; a.stream = (hipStream_t)stream;
+    int rc = check_conv(a, packed_act, packed_wgt);
+    if (rc) return rc;
+    a.wtop = (1 << k_w) - 1;
+    return run_conv(0, a);
+}
+
 int ebs_mixed_conv2d_requant(const void *packed_act, const void *packed_wgt,
                              int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
-                             int k_w, int k_a, const float *scale, const float *offset, int per_channel,
+                             int k_w, int k_a, int signed_weights,
+                             const float *scale, const float *offset, int per_channel,
                              float alpha_next, int k_next, void *packed_next, void *stream)
 {
     if (!packed_next) return EBS_ERR_NULL;
@@ -193,6 +212,7 @@ int ebs_mixed_conv2d_requant(const void *packed_act, const void *packed_wgt,
     if (rc) return rc;
     rc = check_act_shape(N, a.OH, a.OW, K);          // the next layer's packed tensor must be addressable
     if (rc) return rc;
+    a.wtop = signed_weights ? (1 << k_w) - 1 : 0;
     rc = launch_zero_border(a.next, N, a.OH, a.OW, words_per_pixel(K) * k_next, a.stream);
     if (rc) return rc;
     rc = launch_requant_tiled(a);

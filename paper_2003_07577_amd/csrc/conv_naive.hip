@@ -10,6 +10,7 @@ namespace ebs {
 
 struct NaiveGeom {
     int H, W, K, R, S, stride, pad, OH, OW, cw;
+    int wtop;      // 0: unsigned weight levels; else 2^k_w - 1 (signed weights 2q - wtop)
 };
 
 template <int KW, int KA>
@@ -20,6 +21,9 @@ __device__ __forceinline__ int32_t naive_point(const uint32_t *__restrict__ act,
     uint32_t cls[NCLS];
 #pragma unroll
     for (int c = 0; c < NCLS; ++c) cls[c] = 0u;
+    uint32_t wsum[KA];
+#pragma unroll
+    for (int j = 0; j < KA; ++j) wsum[j] = 0u;
     const int RS = g.R * g.S;
     const int cw = g.cw;
     const uint32_t *wk = wgt + ((long long)(k / kWgtGroup) * RS * cw * kWgtGroup + (k % kWgtGroup)) * KW;
@@ -42,12 +46,22 @@ __device__ __forceinline__ int32_t naive_point(const uint32_t *__restrict__ act,
                 for (int i = 0; i < KW; ++i)
 #pragma unroll
                     for (int j = 0; j < KA; ++j) cls[i + j] += __builtin_popcount(q[i] & x[j]);
+                if (g.wtop) {
+#pragma unroll
+                    for (int j = 0; j < KA; ++j) wsum[j] += __builtin_popcount(x[j]);
+                }
             }
         }
     }
     uint32_t acc = 0;
 #pragma unroll
     for (int c = 0; c < NCLS; ++c) acc += cls[c] << c;
+    if (g.wtop) {
+        uint32_t ws = 0;
+#pragma unroll
+        for (int j = 0; j < KA; ++j) ws += wsum[j] << j;
+        return 2 * (int32_t)acc - g.wtop * (int32_t)ws;
+    }
     return (int32_t)acc;
 }
 
@@ -108,7 +122,7 @@ bd_requant_naive(const uint32_t *__restrict__ act, const uint32_t *__restrict__ 
 template <int KW, int KA>
 static int launch(const ConvArgs &a)
 {
-    NaiveGeom g{a.H, a.W, a.K, a.R, a.S, a.stride, a.pad, a.OH, a.OW, a.cw};
+    NaiveGeom g{a.H, a.W, a.K, a.R, a.S, a.stride, a.pad, a.OH, a.OW, a.cw, a.wtop};
     if (a.next) {
         long long total = (long long)a.N * a.OH * a.OW * ((a.K + 31) / 32);
         unsigned blocks = (unsigned)((total + 255) / 256);

@@ -67,6 +67,7 @@ struct TiledShape {
     // fused re-quantisation (REQ kernels only): next layer's quantiser and packed layout
     float alpha, qs;
     int k_next, OHn, OWn, cwn;     // bordered output grid (OH+2, OW+2), words per position of the next layer
+    int wtop;         // 0: unsigned weight levels; else 2^k_w - 1 (signed weights 2q - wtop, Eq. 1a)
     int dbg;          // experiment switches; only read in EBS_EXPERIMENT builds
 };
 
@@ -203,6 +204,13 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
 #pragma unroll
             for (int s = 0; s < C::NCLS; ++s) cls[p][c][s] = 0u;
 
+    // signed weights only: bitcounts of the activation planes alone (the window sum of the levels)
+    uint32_t wsum_cls[PIX][KA];
+#pragma unroll
+    for (int p = 0; p < PIX; ++p)
+#pragma unroll
+        for (int j = 0; j < KA; ++j) wsum_cls[p][j] = 0u;
+
     const int wstride = sh.ucap * C::KAP;     // LDS dwords between consecutive words of a position
     const int rowstride = sh.Wp * C::KAP;     // LDS dwords between filter rows
 
@@ -254,6 +262,12 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
 #pragma unroll
                         for (int j = 0; j < KA; ++j)
                             cls[p][c][i + j] = bcnt_acc(q[c][i] & x[p][j], cls[p][c][i + j]);
+            if (sh.wtop) {      // wave-uniform
+#pragma unroll
+                for (int p = 0; p < PIX; ++p)
+#pragma unroll
+                    for (int j = 0; j < KA; ++j) wsum_cls[p][j] = bcnt_acc(x[p][j], wsum_cls[p][j]);
+            }
         };
         auto rotate = [&](uint32_t (&xc)[PIX][KA], uint32_t (&qc)[KT][KW],
                           const uint32_t (&xn)[PIX][KA], const uint32_t (&qn)[KT][KW]) {
@@ -377,6 +391,18 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
             for (int s = 0; s < C::NCLS; ++s) v += cls[p][c][s] << s;
             acc[p][c] = (int32_t)v;
         }
+    if (sh.wtop) {
+        // integer weights 2q - wtop: 2 * sum(q*a) - wtop * sum(a); linear, so it also holds for the
+        // partial sums of a reduction split among waves
+#pragma unroll
+        for (int p = 0; p < PIX; ++p) {
+            uint32_t ws = 0;
+#pragma unroll
+            for (int j = 0; j < KA; ++j) ws += wsum_cls[p][j] << j;
+#pragma unroll
+            for (int c = 0; c < KT; ++c) acc[p][c] = 2 * acc[p][c] - sh.wtop * (int32_t)ws;
+        }
+    }
 
     // ---- epilogue through LDS: [position][channel] tile, then coalesced write-back
     constexpr int CG = C::OCOLS / 4;              // 16-byte column groups per row
@@ -531,6 +557,7 @@ static int launch_cfg(const ConvArgs &a)
     sh.wgroups = (a.K + kWgtGroup - 1) / kWgtGroup;
     sh.div_ow = make_fastdiv((uint32_t)a.OW);
     sh.div_ohow = make_fastdiv((uint32_t)(a.OH * a.OW));
+    sh.wtop = a.wtop;
     if (REQ) {
         sh.alpha = a.alpha;
         sh.k_next = a.k_next;

@@ -26,6 +26,9 @@ struct ConvArgs {
     uint32_t *next;
     float alpha;           // clip of the next layer's activation quantiser
     int k_next;            // its bitwidth
+    // signed weights (Eq. 1a): 0 = unsigned levels; otherwise 2^k_w - 1, and the kernels return
+    // 2*sum(q*a) - wtop*sum(a), the product with the integer weights 2q - (2^k_w - 1)
+    int wtop;
 };
 
 inline int words_per_pixel(int C) { return (C + 31) / 32; }
