@@ -25,6 +25,10 @@
 //    work-group writes are 4*KT channels wide), or four shares of the reduction
 //    words of one tile (MODE_R4, for layers with few outputs and a long
 //    reduction; the partial sums meet in LDS).
+//  * SGN adds, for the signed-weight form (integer weights 2q - (2^k_w - 1), Eq. 1a), the
+//    bitcounts of the activation planes alone (window sum of the levels) and folds
+//    2*acc - (2^k_w - 1)*window_sum into the epilogue; REQ replaces the int32/fp32 write-back
+//    by the next layer's quantiser and bit-plane packing.
 //  * FS = 3 instantiates the 3x3 filter with the taps of a filter row unrolled
 //    (tap offsets become instruction immediates); FS = 0 is the generic filter.
 //  * the epilogue goes through LDS: accumulators are laid out [position][channel]
@@ -115,7 +119,7 @@ struct Cfg {
     static_assert(256 % (OCOLS / 4) == 0, "write-back assumes a fixed column group per thread");
 };
 
-template <int KW, int KA, int PIX, int KT, int CH, int MODE, int FS, bool REQ>
+template <int KW, int KA, int PIX, int KT, int CH, int MODE, int FS, bool REQ, bool SGN>
 __global__ void __launch_bounds__(256)
 bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
               const float *__restrict__ scale, const float *__restrict__ offset,
@@ -262,7 +266,7 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
 #pragma unroll
                         for (int j = 0; j < KA; ++j)
                             cls[p][c][i + j] = bcnt_acc(q[c][i] & x[p][j], cls[p][c][i + j]);
-            if (sh.wtop) {      // wave-uniform
+            if constexpr (SGN) {
 #pragma unroll
                 for (int p = 0; p < PIX; ++p)
 #pragma unroll
@@ -391,7 +395,7 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
             for (int s = 0; s < C::NCLS; ++s) v += cls[p][c][s] << s;
             acc[p][c] = (int32_t)v;
         }
-    if (sh.wtop) {
+    if constexpr (SGN) {
         // integer weights 2q - wtop: 2 * sum(q*a) - wtop * sum(a); linear, so it also holds for the
         // partial sums of a reduction split among waves
 #pragma unroll
@@ -538,9 +542,10 @@ static constexpr size_t kMaxLdsBytes = 64 * 1024;       // per work-group (dynam
 static constexpr size_t kLdsPerCu = 160 * 1024;         // gfx950
 static constexpr int kNumCus = 256;
 
-template <int KW, int KA, int BUDGET, int CH, int MODE, int FS, bool REQ = false>
+template <int KW, int KA, int BUDGET, int CH, int MODE, int FS, bool REQ = false, bool SGN = false>
 static int launch_cfg(const ConvArgs &a)
 {
+    if ((a.wtop != 0) != SGN) return EBS_ERR_UNSUPPORTED;
     constexpr int PIX = TileOf<BUDGET, KW + KA - 1>::PIX;
     constexpr int KT = TileOf<BUDGET, KW + KA - 1>::KT;
     using C = Cfg<KW, KA, PIX, KT, CH, MODE>;
@@ -597,7 +602,7 @@ static int launch_cfg(const ConvArgs &a)
         if (want > lds_bytes) lds_bytes = want;
     }
 
-    hipLaunchKernelGGL((bd_conv_tiled<KW, KA, PIX, KT, CH, MODE, FS, REQ>), dim3((unsigned)(sh.xcd_chunk * 8)), dim3(256),
+    hipLaunchKernelGGL((bd_conv_tiled<KW, KA, PIX, KT, CH, MODE, FS, REQ, SGN>), dim3((unsigned)(sh.xcd_chunk * 8)), dim3(256),
                        lds_bytes, a.stream, a.act, a.wgt, a.scale, a.offset, a.acc, a.out, a.next, sh);
     return hip_ok(hipGetLastError());
 }
@@ -615,6 +620,18 @@ constexpr int kNumTiledVariants = 18;
 template <int KW, int KA, int FS>
 static int launch_bits(const ConvArgs &a, int v)
 {
+    if (a.wtop) {
+        // signed weights: only the variants the shape heuristic uses are instantiated
+        switch (v) {
+#define EBS_X(idx, b, ch, mode) case idx: return launch_cfg<KW, KA, b, ch, mode, FS, false, true>(a);
+            EBS_X(3, 32, 2, MODE_P4)   EBS_X(4, 32, 1, MODE_P4)   EBS_X(5, 32, 4, MODE_P4)
+            EBS_X(9, 32, 2, MODE_K4)   EBS_X(10, 32, 1, MODE_K4)  EBS_X(11, 32, 4, MODE_K4)
+            EBS_X(12, 16, 2, MODE_K4)  EBS_X(13, 16, 1, MODE_K4)  EBS_X(14, 16, 4, MODE_K4)
+            EBS_X(17, 16, 4, MODE_R4)
+#undef EBS_X
+        }
+        return EBS_ERR_UNSUPPORTED;
+    }
     switch (v) {
 #define EBS_X(idx, b, ch, mode) case idx: return launch_cfg<KW, KA, b, ch, mode, FS>(a);
         EBS_TILED_VARIANTS(EBS_X)
@@ -627,6 +644,14 @@ static int launch_bits(const ConvArgs &a, int v)
 template <int KW, int KA, int FS>
 static int launch_bits_req(const ConvArgs &a, int v)
 {
+    if (a.wtop) {
+        switch (v) {
+            case 0: return launch_cfg<KW, KA, 8, 2, MODE_K4, FS, true, true>(a);
+            case 1: return launch_cfg<KW, KA, 8, 1, MODE_K4, FS, true, true>(a);
+            case 2: return launch_cfg<KW, KA, 8, 4, MODE_K4, FS, true, true>(a);
+        }
+        return EBS_ERR_UNSUPPORTED;
+    }
     switch (v) {
         case 0: return launch_cfg<KW, KA, 8, 2, MODE_K4, FS, true>(a);
         case 1: return launch_cfg<KW, KA, 8, 1, MODE_K4, FS, true>(a);
