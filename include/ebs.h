@@ -59,6 +59,10 @@ int ebs_version(void);
 /* Static, human-readable name of a status code. */
 const char *ebs_status_string(int status);
 
+/* Name of the HIP runtime error behind the calling thread's most recent
+ * EBS_ERR_HIP ("hipSuccess" if there was none).  Static string. */
+const char *ebs_last_hip_error(void);
+
 /*
  * Size in bytes of the packed bit-plane form of a weight tensor (the binary
  * matrix B_w of Eq. 12/15: k_w planes, channel bits packed into 32-bit words)

@@ -22,6 +22,7 @@ from .binding import (  # noqa: F401
     ebs_packed_activations_bytes,
     ebs_packed_weights_bytes,
     ebs_status_string,
+    ebs_last_hip_error,
     ebs_version,
     library_path,
     load_library,

@@ -20,7 +20,8 @@ _ci = ctypes.c_int
 class EbsError(RuntimeError):
     def __init__(self, status: int, what: str):
         self.status = status
-        super().__init__(f"{what}: {ebs_status_string(status)} ({status})")
+        detail = f" [{ebs_last_hip_error()}]" if status == -6 else ""
+        super().__init__(f"{what}: {ebs_status_string(status)} ({status}){detail}")
 
 
 def library_path() -> str:
@@ -35,10 +36,20 @@ def load_library():
             raise FileNotFoundError(
                 f"{_LIB_PATH} is not built; run `python -m paper_2003_07577_amd.build` "
                 "(there is no non-HIP fallback)")
+        # One HIP runtime per process: PyTorch ships its own libamdhip64 and asks for it by
+        # file name, so it must be loaded before libebs.so (which asks by soname and then
+        # shares it).  In the other order two runtimes end up loaded and kernels of the
+        # second one fail with hipErrorNoDevice on pointers of the first.
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         lib = ctypes.CDLL(_LIB_PATH)
         lib.ebs_version.restype = _ci
         lib.ebs_status_string.restype = ctypes.c_char_p
         lib.ebs_status_string.argtypes = [_ci]
+        lib.ebs_last_hip_error.restype = ctypes.c_char_p
+        lib.ebs_last_hip_error.argtypes = []
         lib.ebs_packed_weights_bytes.restype = ctypes.c_size_t
         lib.ebs_packed_weights_bytes.argtypes = [_ci] * 5
         lib.ebs_packed_activations_bytes.restype = ctypes.c_size_t
@@ -105,6 +116,10 @@ def ebs_version() -> int:
 
 def ebs_status_string(status: int) -> str:
     return load_library().ebs_status_string(status).decode()
+
+
+def ebs_last_hip_error() -> str:
+    return load_library().ebs_last_hip_error().decode()
 
 
 def ebs_packed_weights_bytes(K, C, R, S, k_w) -> int:

@@ -8,6 +8,12 @@ int pack_weights(const uint8_t *levels, uint32_t *packed, int K, int C, int RS, 
 int check_levels(const uint8_t *levels, size_t count, int bits, int32_t *flag, hipStream_t st);
 int launch_conv_mfma_i8(const uint8_t *act, const uint8_t *wgt, const ConvArgs &a);
 
+hipError_t &last_hip_error()
+{
+    static thread_local hipError_t e = hipSuccess;
+    return e;
+}
+
 static const long long kMaxElems = (1LL << 31) - 1;
 
 static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -72,6 +78,8 @@ using namespace ebs;
 extern "C" {
 
 int ebs_version(void) { return 100; }
+
+const char *ebs_last_hip_error(void) { return hipGetErrorName(ebs::last_hip_error()); }
 
 const char *ebs_status_string(int s)
 {

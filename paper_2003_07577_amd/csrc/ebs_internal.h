@@ -50,6 +50,13 @@ int launch_requant_tiled(const ConvArgs &a);
 int conv_tiled_variant_count();
 const char *conv_tiled_variant_name(int variant);
 
-inline int hip_ok(hipError_t e) { return e == hipSuccess ? EBS_OK : EBS_ERR_HIP; }
+// Last HIP error this thread's library calls have seen (hipSuccess if none).
+hipError_t &last_hip_error();
+inline int hip_ok(hipError_t e)
+{
+    if (e == hipSuccess) return EBS_OK;
+    last_hip_error() = e;
+    return EBS_ERR_HIP;
+}
 
 }  // namespace ebs

@@ -38,6 +38,7 @@ def test_version_and_status_strings(lib):
     for s in range(-7, 0):
         assert ebs.ebs_status_string(s).startswith("EBS_ERR_")
     assert "unknown" in ebs.ebs_status_string(-99)
+    assert ebs.ebs_last_hip_error() == "hipSuccess"      # no launch has failed in this thread
 
 
 def test_packed_sizes(lib):
