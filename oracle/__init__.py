@@ -262,3 +262,63 @@ def bd_matrix_form(a_nhwc, q_krsc, k_w, k_a, stride=1, pad=0, explicit_lambda=Fa
             for k in range(Kb):
                 O += (P[m::M, k::Kb] << (m + k))                  # stage 2 shift-adds
     return O.T.reshape(N, OH, OW, K_out), P
+
+
+# --------------------------------------------------------------------------
+# The two stages of Sec. 4.3 as separate operations (what a literal
+# implementation materialises between its two convolutions).
+# --------------------------------------------------------------------------
+
+def partial_products(a_nhwc, q_krsc, k_w, k_a, stride=1, pad=0):
+    """Stage 1 of Sec. 4.3: the ordinary convolution with binary weights and binary
+    activations.  Digit m of the weights convolved with digit k of the activations,
+    each as a 0/1 tensor through the direct integer convolution.
+
+    Returns planes[m][k][N][OH][OW][c_o] (int32); planes[m][k][j][i] is the entry
+    p_(i*M+m, j*K+k) of the paper's P (0-based, j = flattened output position).
+    """
+    a = np.asarray(a_nhwc).astype(np.uint8)
+    q = np.asarray(q_krsc).astype(np.uint8)
+    out = None
+    for m in range(k_w):
+        qm = ((q >> m) & 1).astype(np.uint8)
+        for k in range(k_a):
+            ak = ((a >> k) & 1).astype(np.uint8)
+            pm = conv2d_levels(ak, qm, stride, pad)
+            if out is None:
+                out = np.empty((k_w, k_a) + pm.shape, dtype=np.int32)
+            out[m, k] = pm
+    return out
+
+
+def planes_to_matrix(planes):
+    """Layout change only: planes[m][k][...positions...][c_o] -> P of shape (c_o*M, n*K)
+    with row i*M+m and column j*K+k (Sec. 4.3)."""
+    planes = np.asarray(planes)
+    M, Kb = planes.shape[:2]
+    c_o = planes.shape[-1]
+    flat = planes.reshape(M, Kb, -1, c_o)                 # [m][k][j][i]
+    n = flat.shape[2]
+    return np.ascontiguousarray(flat.transpose(3, 0, 2, 1)).reshape(c_o * M, n * Kb)
+
+
+def depthwise_pow2(P, M, Kb):
+    """Stage 2 of Sec. 4.3 (Eq. 14): one depthwise kernel delta_w^T delta_x of
+    shape (M, K), entries 2^(m+k), slid over P with stride (M, K).
+    P is (c_o*M, n*K); returns O (c_o, n) as int64."""
+    P = np.asarray(P, dtype=np.int64)
+    rows, cols = P.shape
+    if rows % M or cols % Kb:
+        raise ValueError("P does not tile into (M, K) windows")
+    kernel = np.empty((M, Kb), dtype=np.int64)
+    for m in range(M):
+        for k in range(Kb):
+            kernel[m, k] = 1 << (m + k)
+    c_o, n = rows // M, cols // Kb
+    O = np.empty((c_o, n), dtype=np.int64)
+    for i in range(c_o):
+        for j in range(n):
+            window = P[i * M:(i + 1) * M, j * Kb:(j + 1) * Kb]
+            O[i, j] = int((window * kernel).sum())
+    return O
+

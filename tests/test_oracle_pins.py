@@ -354,3 +354,59 @@ def test_signed_conv_closed_forms(oracle_mod):
     q[0, 0, 0, 1] = 1                      # weights (-1, +1)
     a2 = np.array([5, 2], np.uint8).reshape(1, 1, 1, 2)
     assert oracle_mod.conv2d_signed_levels(a2, q, 1, 1, 0)[0, 0, 0, 0] == -5 + 2
+
+
+# ---------------------------------------------------------------- two separate stages (Sec. 4.3)
+def test_depthwise_stage_on_hand_fixture(oracle_mod):
+    """The hand-computed P of the worked example goes to its hand-computed O."""
+    g = read_sections("bd_worked_example_2x3_3x2.txt")
+    assert np.array_equal(oracle_mod.depthwise_pow2(g["P"], 2, 2), g["O"])
+
+
+def test_depthwise_stage_closed_forms(oracle_mod):
+    # all-ones P: every window sums the whole kernel, (2^M - 1)(2^K - 1)
+    for M, Kb in [(1, 1), (2, 3), (4, 4), (3, 1)]:
+        O = oracle_mod.depthwise_pow2(np.ones((5 * M, 7 * Kb), dtype=np.int64), M, Kb)
+        assert O.shape == (5, 7) and (O == ((1 << M) - 1) * ((1 << Kb) - 1)).all()
+    # a single non-zero entry lands in exactly one output with weight 2^(m+k): catches a
+    # transposed kernel, a wrong stride or swapped window axes (M != K on purpose)
+    M, Kb, c_o, n = 3, 2, 4, 5
+    for (i, m, j, k) in [(0, 0, 0, 0), (3, 2, 4, 1), (1, 2, 2, 0), (2, 0, 3, 1)]:
+        P = np.zeros((c_o * M, n * Kb), dtype=np.int64)
+        P[i * M + m, j * Kb + k] = 7
+        O = oracle_mod.depthwise_pow2(P, M, Kb)
+        want = np.zeros((c_o, n), dtype=np.int64)
+        want[i, j] = 7 << (m + k)
+        assert np.array_equal(O, want)
+    with pytest.raises(ValueError):
+        oracle_mod.depthwise_pow2(np.zeros((5, 4)), 2, 2)
+
+
+def test_depthwise_stage_is_lambda_products(oracle_mod):
+    """Eq. 13: O = Lambda_w P Lambda_x^T with the block-diagonal coefficient matrices."""
+    rng = np.random.default_rng(4130)
+    M, Kb, c_o, n = 3, 4, 3, 6
+    P = rng.integers(0, 50, (c_o * M, n * Kb))
+    Lw = np.kron(np.eye(c_o, dtype=np.int64), (2 ** np.arange(M))[None, :])
+    Lx = np.kron(np.eye(n, dtype=np.int64), (2 ** np.arange(Kb))[None, :])
+    assert np.array_equal(oracle_mod.depthwise_pow2(P, M, Kb), Lw @ P @ Lx.T)
+
+
+@pytest.mark.parametrize("kw,ka", [(1, 1), (2, 3), (4, 4), (3, 1), (1, 4)])
+def test_partial_products_match_bitwise_and_matrix_forms(oracle_mod, kw, ka):
+    N, C, H, W, K, R, S, st, pad = 2, 7, 6, 5, 5, 3, 2, 2, 1
+    a, q = _rand(500 + kw * 5 + ka, N, C, H, W, K, R, S, kw, ka)
+    planes = oracle_mod.partial_products(a, q, kw, ka, st, pad)
+    OH, OW = oracle_mod.out_dims(H, W, R, S, st, pad)
+    assert planes.shape == (kw, ka, N, OH, OW, K)
+    # bit-by-bit AND/bitcount route (Eq. 2), stored [n][oh][ow][k][m][kk]
+    _, bitwise = oracle_mod.bitplane_conv(a, q, kw, ka, st, pad, return_planes=True)
+    assert np.array_equal(planes, bitwise.transpose(4, 5, 0, 1, 2, 3))
+    # matrix route: P = B_w B_x
+    O, P = oracle_mod.bd_matrix_form(a, q, kw, ka, st, pad)
+    Pm = oracle_mod.planes_to_matrix(planes)
+    assert np.array_equal(Pm, P)
+    # and the two stages chained give the direct convolution
+    O2 = oracle_mod.depthwise_pow2(Pm, kw, ka)
+    assert np.array_equal(O2.T.reshape(N, OH, OW, K), oracle_mod.conv2d_levels(a, q, st, pad))
+
