@@ -149,6 +149,35 @@ int ebs_mixed_conv2d_signed(const void *packed_act, const void *packed_wgt,
                             int32_t *acc_out, float *out_f32, void *stream);
 
 /*
+ * The literal two-stage form of Sec. 4.3, as a measured comparison with the fused call: the
+ * intermediate P that ebs_mixed_conv2d keeps in registers goes through device memory here.
+ *
+ * Stage 1, ebs_binary_conv_planes: the ordinary convolution with binary weights and binary
+ * activations (Eq. 13, P = B_w B_x; AND + bitcount only, no shifts).
+ *   planes : out, device, int32, ebs_partial_products_bytes(...) bytes, 16-byte aligned.
+ *            k_w*k_a tensors [N][OH][OW][K] in the order m*k_a + k (m: weight digit, k:
+ *            activation digit).  Entry p_(i*M+m, j*K+k) of the paper's (c_o M) x (n K) matrix,
+ *            i = output channel and j = flattened output position (n, oh, ow), is element
+ *            [j][i] of plane (m, k).
+ * Stage 2, ebs_pow2_depthwise: the depthwise convolution of P with the single kernel
+ * delta_w^T delta_x of shape (M, K), entries 2^(m+k), stride (M, K) (Eq. 14), then the affine
+ * epilogue of ebs_mixed_conv2d:
+ *   acc_out[j][i] = sum_m sum_k planes[m*k_a + k][j][i] << (m + k);  out_f32 = scale*acc + offset.
+ *   positions = N*OH*OW; scale/offset/per_channel/acc_out/out_f32 as for ebs_mixed_conv2d.
+ * ebs_partial_products_bytes returns 0 on invalid arguments.  Other arguments and error codes as
+ * for ebs_mixed_conv2d; nothing is allocated by either call.
+ */
+size_t ebs_partial_products_bytes(int N, int H, int W, int K, int R, int S,
+                                  int stride, int pad, int k_w, int k_a);
+int ebs_binary_conv_planes(const void *packed_act, const void *packed_wgt,
+                           int N, int C, int H, int W, int K, int R, int S,
+                           int stride, int pad, int k_w, int k_a,
+                           int32_t *planes, void *stream);
+int ebs_pow2_depthwise(const int32_t *planes, long long positions, int K, int k_w, int k_a,
+                       const float *scale, const float *offset, int per_channel,
+                       int32_t *acc_out, float *out_f32, void *stream);
+
+/*
  * Same call with the kernel variant chosen by the caller instead of the
  * library's shape heuristic; exists so that measurements can sweep tilings.
  * variant 0 = heuristic; ebs_conv_variant_count() gives the number of

@@ -13,6 +13,9 @@ from .binding import (  # noqa: F401
     ebs_mixed_conv2d_mfma_i8,
     ebs_mixed_conv2d_requant,
     ebs_mixed_conv2d_signed,
+    ebs_partial_products_bytes,
+    ebs_binary_conv_planes,
+    ebs_pow2_depthwise,
     ebs_mixed_conv2d_variant,
     ebs_pack_activations,
     ebs_pack_weights,

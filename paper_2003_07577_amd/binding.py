@@ -67,6 +67,12 @@ def load_library():
         lib.ebs_mixed_conv2d_requant.argtypes = [_vp, _vp] + [_ci] * 12 + [_vp, _vp, _ci, ctypes.c_float, _ci, _vp, _vp]
         lib.ebs_mixed_conv2d_signed.restype = _ci
         lib.ebs_mixed_conv2d_signed.argtypes = conv_tail
+        lib.ebs_partial_products_bytes.restype = ctypes.c_size_t
+        lib.ebs_partial_products_bytes.argtypes = [_ci] * 10
+        lib.ebs_binary_conv_planes.restype = _ci
+        lib.ebs_binary_conv_planes.argtypes = [_vp, _vp] + [_ci] * 11 + [_vp, _vp]
+        lib.ebs_pow2_depthwise.restype = _ci
+        lib.ebs_pow2_depthwise.argtypes = [_vp, ctypes.c_longlong, _ci, _ci, _ci, _vp, _vp, _ci, _vp, _vp, _vp]
         lib.ebs_conv_variant_count.restype = _ci
         lib.ebs_conv_variant_name.restype = ctypes.c_char_p
         lib.ebs_conv_variant_name.argtypes = [_ci]
@@ -161,6 +167,30 @@ def ebs_mixed_conv2d_signed(packed_act, packed_wgt, N, C, H, W, K, R, S, stride,
         _ptr(scale), _ptr(offset), int(bool(per_channel)), _ptr(acc_out), _ptr(out_f32), _stream(stream))
     if check:
         _check(rc, "ebs_mixed_conv2d_signed")
+    return rc
+
+
+def ebs_partial_products_bytes(N, H, W, K, R, S, stride, pad, k_w, k_a) -> int:
+    return load_library().ebs_partial_products_bytes(N, H, W, K, R, S, stride, pad, k_w, k_a)
+
+
+def ebs_binary_conv_planes(packed_act, packed_wgt, N, C, H, W, K, R, S, stride, pad, k_w, k_a,
+                           planes, stream=None, check=True) -> int:
+    rc = load_library().ebs_binary_conv_planes(
+        _ptr(packed_act), _ptr(packed_wgt), N, C, H, W, K, R, S, stride, pad, k_w, k_a,
+        _ptr(planes), _stream(stream))
+    if check:
+        _check(rc, "ebs_binary_conv_planes")
+    return rc
+
+
+def ebs_pow2_depthwise(planes, positions, K, k_w, k_a, scale, offset, per_channel, acc_out, out_f32,
+                       stream=None, check=True) -> int:
+    rc = load_library().ebs_pow2_depthwise(
+        _ptr(planes), positions, K, k_w, k_a, _ptr(scale), _ptr(offset), int(bool(per_channel)),
+        _ptr(acc_out), _ptr(out_f32), _stream(stream))
+    if check:
+        _check(rc, "ebs_pow2_depthwise")
     return rc
 
 

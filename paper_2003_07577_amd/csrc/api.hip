@@ -39,9 +39,9 @@ static int check_wgt_shape(int K, int C, int R, int S)
 }
 
 // Validates a convolution request and fills the geometry fields.
-static int check_conv(ConvArgs &a, const void *p0, const void *p1)
+static int check_conv(ConvArgs &a, const void *p0, const void *p1, bool need_scale = true)
 {
-    if (!p0 || !p1 || !a.scale || (!a.acc && !a.next)) return EBS_ERR_NULL;
+    if (!p0 || !p1 || (need_scale && !a.scale) || (!a.acc && !a.next)) return EBS_ERR_NULL;
     if (!bits_ok(a.kw) || !bits_ok(a.ka)) return EBS_ERR_BITWIDTH;
     int rc = check_act_shape(a.N, a.H, a.W, a.C);
     if (rc) return rc;
@@ -164,6 +164,48 @@ int ebs_mixed_conv2d(const void *packed_act, const void *packed_wgt,
 {
     return ebs_mixed_conv2d_variant(0, packed_act, packed_wgt, N, C, H, W, K, R, S, stride, pad, k_w, k_a,
                                     scale, offset, per_channel, acc_out, out_f32, stream);
+}
+
+size_t ebs_partial_products_bytes(int N, int H, int W, int K, int R, int S, int stride, int pad, int k_w, int k_a)
+{
+    if (!bits_ok(k_w) || !bits_ok(k_a)) return 0;
+    if (N <= 0 || H <= 0 || W <= 0 || K <= 0 || R <= 0 || S <= 0 || stride <= 0 || pad < 0) return 0;
+    if (pad >= R || pad >= S || H + 2 * pad < R || W + 2 * pad < S) return 0;
+    long long OH = (H + 2 * pad - R) / stride + 1, OW = (W + 2 * pad - S) / stride + 1;
+    long long elems = (long long)N * OH * OW;
+    if (elems > kMaxElems || elems * K > kMaxElems) return 0;
+    return (size_t)elems * K * k_w * k_a * sizeof(int32_t);
+}
+
+int ebs_binary_conv_planes(const void *packed_act, const void *packed_wgt,
+                           int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                           int k_w, int k_a, int32_t *planes, void *stream)
+{
+    ConvArgs a{};
+    a.act = (const uint32_t *)packed_act;
+    a.wgt = (const uint32_t *)packed_wgt;
+    a.N = N; a.C = C; a.H = H; a.W = W; a.K = K; a.R = R; a.S = S;
+    a.stride = stride; a.pad = pad; a.kw = k_w; a.ka = k_a;
+    a.acc = planes; a.stream = (hipStream_t)stream;
+    int rc = check_conv(a, packed_act, packed_wgt, false);
+    if (rc) return rc;
+    rc = launch_planes_tiled(a);
+    if (rc == EBS_ERR_UNSUPPORTED) rc = launch_planes_naive(a);
+    return rc;
+}
+
+int ebs_pow2_depthwise(const int32_t *planes, long long positions, int K, int k_w, int k_a,
+                       const float *scale, const float *offset, int per_channel,
+                       int32_t *acc_out, float *out_f32, void *stream)
+{
+    if (!planes || !scale || !acc_out) return EBS_ERR_NULL;
+    if (!bits_ok(k_w) || !bits_ok(k_a)) return EBS_ERR_BITWIDTH;
+    if (positions <= 0 || K <= 0 || positions > kMaxElems || positions * K > kMaxElems) return EBS_ERR_SHAPE;
+    if (!aligned16(planes) || !aligned16(acc_out) || (out_f32 && !aligned16(out_f32))) return EBS_ERR_ALIGN;
+    if ((reinterpret_cast<uintptr_t>(scale) & 3u) || (offset && (reinterpret_cast<uintptr_t>(offset) & 3u)))
+        return EBS_ERR_ALIGN;
+    return launch_pow2_depthwise(planes, positions * K, K, k_w, k_a, scale, offset, per_channel ? 1 : 0,
+                                 acc_out, out_f32, (hipStream_t)stream);
 }
 
 int ebs_mixed_conv2d_mfma_i8(const uint8_t *act_levels, const uint8_t *wgt_levels,

@@ -6,7 +6,10 @@ namespace ebs {
 
 template <int KW, int FS> int launch_tiled_kw(const ConvArgs &a, int v);
 template <int KW, int FS> int launch_tiled_req_kw(const ConvArgs &a, int v);
+template <int KW, int FS> int launch_tiled_planes_kw(const ConvArgs &a, int v);
 #define EBS_DECL(kw) \
+    template <> int launch_tiled_planes_kw<kw, 0>(const ConvArgs &a, int v); \
+    template <> int launch_tiled_planes_kw<kw, 3>(const ConvArgs &a, int v); \
     template <> int launch_tiled_kw<kw, 0>(const ConvArgs &a, int v); \
     template <> int launch_tiled_kw<kw, 3>(const ConvArgs &a, int v); \
     template <> int launch_tiled_req_kw<kw, 0>(const ConvArgs &a, int v); \
@@ -58,6 +61,29 @@ static int run_req_fs(const ConvArgs &a, int v)
         case 4: return launch_tiled_req_kw<4, FS>(a, v);
     }
     return EBS_ERR_BITWIDTH;
+}
+
+template <int FS>
+static int run_planes_fs(const ConvArgs &a, int v)
+{
+    switch (a.kw) {
+        case 1: return launch_tiled_planes_kw<1, FS>(a, v);
+        case 2: return launch_tiled_planes_kw<2, FS>(a, v);
+        case 3: return launch_tiled_planes_kw<3, FS>(a, v);
+        case 4: return launch_tiled_planes_kw<4, FS>(a, v);
+    }
+    return EBS_ERR_BITWIDTH;
+}
+
+// Stage 1 of the two-stage form: four-word chunks when the words per position allow, else single words.
+int launch_planes_tiled(const ConvArgs &a)
+{
+    const int order[2] = {a.cw % 4 == 0 ? 1 : 0, 0};
+    for (int i = 0; i < 2; ++i) {
+        int rc = (a.R == 3 && a.S == 3) ? run_planes_fs<3>(a, order[i]) : run_planes_fs<0>(a, order[i]);
+        if (rc != EBS_ERR_UNSUPPORTED) return rc;
+    }
+    return EBS_ERR_UNSUPPORTED;
 }
 
 // Slot of the chunk size inside a family of three: order ch2, ch1, ch4.

@@ -29,6 +29,9 @@
 //    bitcounts of the activation planes alone (window sum of the levels) and folds
 //    2*acc - (2^k_w - 1)*window_sum into the epilogue; REQ replaces the int32/fp32 write-back
 //    by the next layer's quantiser and bit-plane packing.
+//  * MODE_PL (waves arranged as in MODE_K4) is stage 1 of the literal two-stage form of
+//    Sec. 4.3 alone: one accumulator per plane pair (m, k) instead of per shift class, no
+//    recombination; the k_w*k_a partial-product planes P are written out as int32 tensors.
 //  * FS = 3 instantiates the 3x3 filter with the taps of a filter row unrolled
 //    (tap offsets become instruction immediates); FS = 0 is the generic filter.
 //  * the epilogue goes through LDS: accumulators are laid out [position][channel]
@@ -46,7 +49,7 @@
 
 namespace ebs {
 
-enum { MODE_P4 = 0, MODE_K4 = 1, MODE_R4 = 2 };
+enum { MODE_P4 = 0, MODE_K4 = 1, MODE_R4 = 2, MODE_PL = 3 };
 
 // Experiment builds (-DEBS_EXPERIMENT) can switch phases of the kernel off through the
 // EBS_EXP_DBG environment variable to time them; production builds compile this away.
@@ -95,11 +98,12 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 template <int KW, int KA, int PIX, int KT, int CH, int MODE>
 struct Cfg {
-    static constexpr int NCLS = KW + KA - 1;
+    static constexpr bool PLN = MODE == MODE_PL;     // keep the plane pairs apart (stage 1 of Sec. 4.3 only)
+    static constexpr int NCLS = PLN ? KW * KA : KW + KA - 1;     // accumulators per output
     static constexpr int KAP = (KA == 3) ? 4 : KA;   // planes per staged word, padded to a power of two
     static constexpr int WAVES = 4;
     static constexpr int WPX = MODE == MODE_P4 ? 4 : 1;          // waves along the position axis
-    static constexpr int WK = MODE == MODE_K4 ? 4 : 1;           // waves along the channel axis
+    static constexpr int WK = (MODE == MODE_K4 || PLN) ? 4 : 1;           // waves along the channel axis
     static constexpr int WRED = MODE == MODE_R4 ? 4 : 1;         // waves sharing one reduction
     static constexpr int TPW = 64 * PIX;             // positions per wave
     static constexpr int TP = WPX * TPW;             // positions per work-group
@@ -145,7 +149,7 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wpx = MODE == MODE_P4 ? wave : 0;     // position sub-tile of this wave
-    const int wk = MODE == MODE_K4 ? wave : 0;      // channel sub-tile of this wave
+    const int wk = (MODE == MODE_K4 || MODE == MODE_PL) ? wave : 0;      // channel sub-tile of this wave
     const int wred = MODE == MODE_R4 ? wave : 0;    // share of the reduction words
     const int R = FS > 0 ? FS : sh.R;
     const int S = FS > 0 ? FS : sh.S;
@@ -265,7 +269,10 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
                     for (int i = 0; i < KW; ++i)
 #pragma unroll
                         for (int j = 0; j < KA; ++j)
-                            cls[p][c][i + j] = bcnt_acc(q[c][i] & x[p][j], cls[p][c][i + j]);
+                        {
+                            const int a_idx = C::PLN ? i * KA + j : i + j;
+                            cls[p][c][a_idx] = bcnt_acc(q[c][i] & x[p][j], cls[p][c][a_idx]);
+                        }
             if constexpr (SGN) {
 #pragma unroll
                 for (int p = 0; p < PIX; ++p)
@@ -384,30 +391,6 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
         }
     }
 
-    // ---- Eq. 14: recombine the shift classes
-    int32_t acc[PIX][KT];
-#pragma unroll
-    for (int p = 0; p < PIX; ++p)
-#pragma unroll
-        for (int c = 0; c < KT; ++c) {
-            uint32_t v = 0;
-#pragma unroll
-            for (int s = 0; s < C::NCLS; ++s) v += cls[p][c][s] << s;
-            acc[p][c] = (int32_t)v;
-        }
-    if constexpr (SGN) {
-        // integer weights 2q - wtop: 2 * sum(q*a) - wtop * sum(a); linear, so it also holds for the
-        // partial sums of a reduction split among waves
-#pragma unroll
-        for (int p = 0; p < PIX; ++p) {
-            uint32_t ws = 0;
-#pragma unroll
-            for (int j = 0; j < KA; ++j) ws += wsum_cls[p][j] << j;
-#pragma unroll
-            for (int c = 0; c < KT; ++c) acc[p][c] = 2 * acc[p][c] - sh.wtop * (int32_t)ws;
-        }
-    }
-
     // ---- epilogue through LDS: [position][channel] tile, then coalesced write-back
     constexpr int CG = C::OCOLS / 4;              // 16-byte column groups per row
     constexpr int RSTEP = 256 / CG;               // rows covered by one sweep of the work-group
@@ -418,98 +401,132 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
     for (int e = 0; e < 4; ++e) {
         const int k = kq + e < sh.K ? kq + e : sh.K - 1;
         const int ci = sh.per_channel ? k : 0;
-        sc[e] = scale[ci];
-        of[e] = offset ? offset[ci] : 0.0f;
+        sc[e] = C::PLN ? 0.0f : scale[ci];                   // the plane kernels take no scales
+        of[e] = (!C::PLN && offset) ? offset[ci] : 0.0f;
     }
     const bool vec_ok = ((sh.K & 3) == 0) && (kq + 3 < sh.K);
     const int my_row = wpx * 64 + lane;
     const int my_col = wk * KT;
 
+    // one pass per partial-product plane (stage 1 of Sec. 4.3 alone), else a single pass
+    constexpr int NPL = C::PLN ? KW * KA : 1;
 #pragma unroll
-    for (int p = 0; p < PIX; ++p) {
-        if (p > 0) __syncthreads();               // the previous pass has been written back
-        if constexpr (MODE == MODE_R4) {
-            // partial sums of the four waves meet in the tile
-            if (wave == 0) {
+    for (int pl = 0; pl < NPL; ++pl) {
+        int32_t *__restrict__ dst_acc = acc_out + (C::PLN ? (size_t)pl * (size_t)sh.total * (size_t)sh.K : 0);
+        // ---- Eq. 14: recombine the shift classes
+        int32_t acc[PIX][KT];
+#pragma unroll
+        for (int p = 0; p < PIX; ++p)
+#pragma unroll
+            for (int c = 0; c < KT; ++c) {
+                uint32_t v = 0;
+                if constexpr (C::PLN) {
+                    v = cls[p][c][pl];                 // stage 1 only: plane pair pl = m*k_a + k as it is
+                } else {
+#pragma unroll
+                    for (int s = 0; s < C::NCLS; ++s) v += cls[p][c][s] << s;
+                }
+                acc[p][c] = (int32_t)v;
+            }
+        if constexpr (SGN) {
+            // integer weights 2q - wtop: 2 * sum(q*a) - wtop * sum(a); linear, so it also holds for the
+            // partial sums of a reduction split among waves
+#pragma unroll
+            for (int p = 0; p < PIX; ++p) {
+                uint32_t ws = 0;
+#pragma unroll
+                for (int j = 0; j < KA; ++j) ws += wsum_cls[p][j] << j;
+#pragma unroll
+                for (int c = 0; c < KT; ++c) acc[p][c] = 2 * acc[p][c] - sh.wtop * (int32_t)ws;
+            }
+        }
+
+#pragma unroll
+        for (int p = 0; p < PIX; ++p) {
+            if (p > 0 || pl > 0) __syncthreads();     // the previous pass has been written back
+            if constexpr (MODE == MODE_R4) {
+                // partial sums of the four waves meet in the tile
+                if (wave == 0) {
+#pragma unroll
+                    for (int c = 0; c < KT; c += 4) {
+                        i32x4 v = {acc[p][c], acc[p][c + 1], acc[p][c + 2], acc[p][c + 3]};
+                        *reinterpret_cast<i32x4 *>(otile + my_row * C::OPITCH + c) = v;
+                    }
+                }
+                __syncthreads();
+                if (wave != 0) {
+#pragma unroll
+                    for (int c = 0; c < KT; ++c) atomicAdd(&otile[my_row * C::OPITCH + c], acc[p][c]);
+                }
+            } else {
 #pragma unroll
                 for (int c = 0; c < KT; c += 4) {
                     i32x4 v = {acc[p][c], acc[p][c + 1], acc[p][c + 2], acc[p][c + 3]};
-                    *reinterpret_cast<i32x4 *>(otile + my_row * C::OPITCH + c) = v;
+                    *reinterpret_cast<i32x4 *>(otile + my_row * C::OPITCH + my_col + c) = v;
                 }
             }
             __syncthreads();
-            if (wave != 0) {
+            if (EBS_DBG(1)) continue;
+            // rows of this pass: row r of sub-tile w is position t_first + w*TPW + p*64 + r
+            if constexpr (REQ) {
+                // ---- fused re-quantisation (Eq. 1b-1c) and bit-plane packing for the next layer: the 8
+                //      threads that hold the 32 channels of one word OR their 4-bit pieces together
+                static_assert(!REQ || (CG % 8 == 0), "a packed word needs all 32 channels in one work-group");
 #pragma unroll
-                for (int c = 0; c < KT; ++c) atomicAdd(&otile[my_row * C::OPITCH + c], acc[p][c]);
-            }
-        } else {
+                for (int r0 = 0; r0 < C::OROWS; r0 += RSTEP) {
+                    const int row = r0 + tid / CG;
+                    const int t = t_first + (row >> 6) * C::TPW + p * 64 + (row & 63);
+                    const bool valid = row < C::OROWS && t < sh.total;
+                    const int rr = row < C::OROWS ? row : 0;
+                    const i32x4 v = *reinterpret_cast<const i32x4 *>(otile + rr * C::OPITCH + cg * 4);
+                    uint32_t lv[4];
 #pragma unroll
-            for (int c = 0; c < KT; c += 4) {
-                i32x4 v = {acc[p][c], acc[p][c + 1], acc[p][c + 2], acc[p][c + 3]};
-                *reinterpret_cast<i32x4 *>(otile + my_row * C::OPITCH + my_col + c) = v;
-            }
-        }
-        __syncthreads();
-        if (EBS_DBG(1)) continue;
-        // rows of this pass: row r of sub-tile w is position t_first + w*TPW + p*64 + r
-        if constexpr (REQ) {
-            // ---- fused re-quantisation (Eq. 1b-1c) and bit-plane packing for the next layer: the 8
-            //      threads that hold the 32 channels of one word OR their 4-bit pieces together
-            static_assert(!REQ || (CG % 8 == 0), "a packed word needs all 32 channels in one work-group");
+                    for (int e = 0; e < 4; ++e)
+                        lv[e] = kq + e < sh.K ? requant_level(v[e], sc[e], of[e], sh.alpha, sh.qs) : 0u;
+                    const int tc = valid ? t : t_first;
+                    const int n = (int)fd_div((uint32_t)tc, sh.div_ohow);
+                    const int rem = tc - n * (int)sh.div_ohow.d;
+                    const int oh = (int)fd_div((uint32_t)rem, sh.div_ow);
+                    const int ow = rem - oh * sh.OW;
+                    const size_t pos = ((size_t)n * sh.OHn + oh + kActBorder) * sh.OWn + ow + kActBorder;
+                    const int word = kq >> 5;
+                    uint32_t *dst = packed_next + (pos * sh.cwn + word) * sh.k_next;
+                    for (int j = 0; j < sh.k_next; ++j) {
+                        uint32_t w = (((lv[0] >> j) & 1u) | (((lv[1] >> j) & 1u) << 1) | (((lv[2] >> j) & 1u) << 2) |
+                                      (((lv[3] >> j) & 1u) << 3)) << (4 * (cg & 7));
+                        w |= (uint32_t)__shfl_xor((int)w, 1);
+                        w |= (uint32_t)__shfl_xor((int)w, 2);
+                        w |= (uint32_t)__shfl_xor((int)w, 4);
+                        if (valid && (cg & 7) == 0 && word < sh.cwn) dst[j] = w;
+                    }
+                }
+            } else {
 #pragma unroll
             for (int r0 = 0; r0 < C::OROWS; r0 += RSTEP) {
                 const int row = r0 + tid / CG;
                 const int t = t_first + (row >> 6) * C::TPW + p * 64 + (row & 63);
-                const bool valid = row < C::OROWS && t < sh.total;
-                const int rr = row < C::OROWS ? row : 0;
-                const i32x4 v = *reinterpret_cast<const i32x4 *>(otile + rr * C::OPITCH + cg * 4);
-                uint32_t lv[4];
+                if (row < C::OROWS && t < sh.total && kq < sh.K) {
+                    const i32x4 v = *reinterpret_cast<const i32x4 *>(otile + row * C::OPITCH + cg * 4);
+                    const size_t o = (size_t)t * sh.K + kq;
+                    if (vec_ok) {
+                        *reinterpret_cast<i32x4 *>(dst_acc + o) = v;
+                        if (!C::PLN && out_f32 && !EBS_DBG(8)) {
+                            f32x4 f = {fmaf((float)v[0], sc[0], of[0]), fmaf((float)v[1], sc[1], of[1]),
+                                       fmaf((float)v[2], sc[2], of[2]), fmaf((float)v[3], sc[3], of[3])};
+                            *reinterpret_cast<f32x4 *>(out_f32 + o) = f;
+                        }
+                    } else {
 #pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    lv[e] = kq + e < sh.K ? requant_level(v[e], sc[e], of[e], sh.alpha, sh.qs) : 0u;
-                const int tc = valid ? t : t_first;
-                const int n = (int)fd_div((uint32_t)tc, sh.div_ohow);
-                const int rem = tc - n * (int)sh.div_ohow.d;
-                const int oh = (int)fd_div((uint32_t)rem, sh.div_ow);
-                const int ow = rem - oh * sh.OW;
-                const size_t pos = ((size_t)n * sh.OHn + oh + kActBorder) * sh.OWn + ow + kActBorder;
-                const int word = kq >> 5;
-                uint32_t *dst = packed_next + (pos * sh.cwn + word) * sh.k_next;
-                for (int j = 0; j < sh.k_next; ++j) {
-                    uint32_t w = (((lv[0] >> j) & 1u) | (((lv[1] >> j) & 1u) << 1) | (((lv[2] >> j) & 1u) << 2) |
-                                  (((lv[3] >> j) & 1u) << 3)) << (4 * (cg & 7));
-                    w |= (uint32_t)__shfl_xor((int)w, 1);
-                    w |= (uint32_t)__shfl_xor((int)w, 2);
-                    w |= (uint32_t)__shfl_xor((int)w, 4);
-                    if (valid && (cg & 7) == 0 && word < sh.cwn) dst[j] = w;
-                }
-            }
-        } else {
-#pragma unroll
-        for (int r0 = 0; r0 < C::OROWS; r0 += RSTEP) {
-            const int row = r0 + tid / CG;
-            const int t = t_first + (row >> 6) * C::TPW + p * 64 + (row & 63);
-            if (row < C::OROWS && t < sh.total && kq < sh.K) {
-                const i32x4 v = *reinterpret_cast<const i32x4 *>(otile + row * C::OPITCH + cg * 4);
-                const size_t o = (size_t)t * sh.K + kq;
-                if (vec_ok) {
-                    *reinterpret_cast<i32x4 *>(acc_out + o) = v;
-                    if (out_f32 && !EBS_DBG(8)) {
-                        f32x4 f = {fmaf((float)v[0], sc[0], of[0]), fmaf((float)v[1], sc[1], of[1]),
-                                   fmaf((float)v[2], sc[2], of[2]), fmaf((float)v[3], sc[3], of[3])};
-                        *reinterpret_cast<f32x4 *>(out_f32 + o) = f;
-                    }
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        if (kq + e < sh.K) {
-                            acc_out[o + e] = v[e];
-                            if (out_f32 && !EBS_DBG(8)) out_f32[o + e] = fmaf((float)v[e], sc[e], of[e]);
+                        for (int e = 0; e < 4; ++e) {
+                            if (kq + e < sh.K) {
+                                dst_acc[o + e] = v[e];
+                                if (!C::PLN && out_f32 && !EBS_DBG(8)) out_f32[o + e] = fmaf((float)v[e], sc[e], of[e]);
+                            }
                         }
                     }
                 }
             }
-        }
+            }
         }
     }
 #ifdef EBS_EXPERIMENT
@@ -538,6 +555,21 @@ EBS_TILE(8, 1, 1, 16)   EBS_TILE(8, 2, 1, 8)    EBS_TILE(8, 3, 1, 8)   EBS_TILE(
 EBS_TILE(8, 5, 1, 8)    EBS_TILE(8, 6, 1, 8)    EBS_TILE(8, 7, 1, 8)
 #undef EBS_TILE
 
+// Tile of a (budget, k_w, k_a) kernel.  Budget 4 is the plane-pair kernel (MODE_PL): one
+// position per lane and as many channels as k_w*k_a accumulators per output (<= 64 per lane)
+// and the weight words per channel (<= 32 scalar registers per operand buffer) allow.
+template <int BUDGET, int KW, int KA> struct TileSel {
+    static constexpr int PIX = TileOf<BUDGET, KW + KA - 1>::PIX;
+    static constexpr int KT = TileOf<BUDGET, KW + KA - 1>::KT;
+};
+template <int KW, int KA> struct TileSel<4, KW, KA> {
+    static constexpr int PIX = 1;
+    static constexpr int KT_ACC = KW * KA <= 4 ? 16 : (KW * KA <= 8 ? 8 : 4);
+    static constexpr int QW = KW * (KW * KA <= 2 ? 2 : 1);     // weight words per channel and step (two-word steps)
+    static constexpr int KT_SGPR = 32 / QW >= 16 ? 16 : (32 / QW >= 8 ? 8 : 4);
+    static constexpr int KT = KT_ACC < KT_SGPR ? KT_ACC : KT_SGPR;
+};
+
 static constexpr size_t kMaxLdsBytes = 64 * 1024;       // per work-group (dynamic LDS without opt-in)
 static constexpr size_t kLdsPerCu = 160 * 1024;         // gfx950
 static constexpr int kNumCus = 256;
@@ -546,8 +578,8 @@ template <int KW, int KA, int BUDGET, int CH, int MODE, int FS, bool REQ = false
 static int launch_cfg(const ConvArgs &a)
 {
     if ((a.wtop != 0) != SGN) return EBS_ERR_UNSUPPORTED;
-    constexpr int PIX = TileOf<BUDGET, KW + KA - 1>::PIX;
-    constexpr int KT = TileOf<BUDGET, KW + KA - 1>::KT;
+    constexpr int PIX = TileSel<BUDGET, KW, KA>::PIX;
+    constexpr int KT = TileSel<BUDGET, KW, KA>::KT;
     using C = Cfg<KW, KA, PIX, KT, CH, MODE>;
     if (a.pad > kActBorder) return EBS_ERR_UNSUPPORTED;   // taps would leave the stored zero ring
     if (a.cw % CH != 0) return EBS_ERR_UNSUPPORTED;       // chunks are whole: no ragged last chunk
@@ -660,9 +692,23 @@ static int launch_bits_req(const ConvArgs &a, int v)
     return EBS_ERR_UNSUPPORTED;
 }
 
+// Plane-pair kernels (stage 1 of the two-stage form): chunk sizes 1 / 4 (variant 0 / 1); the
+// planes are written where ConvArgs::acc points.
+template <int KW, int KA, int FS>
+static int launch_bits_planes(const ConvArgs &a, int v)
+{
+    if (a.wtop) return EBS_ERR_UNSUPPORTED;
+    switch (v) {
+        case 0: return launch_cfg<KW, KA, 4, 1, MODE_PL, FS>(a);
+        case 1: return launch_cfg<KW, KA, 4, 4, MODE_PL, FS>(a);
+    }
+    return EBS_ERR_UNSUPPORTED;
+}
+
 // One translation unit per (weight bitwidth, filter specialisation) instantiates these.
 template <int KW, int FS> int launch_tiled_kw(const ConvArgs &a, int v);
 template <int KW, int FS> int launch_tiled_req_kw(const ConvArgs &a, int v);
+template <int KW, int FS> int launch_tiled_planes_kw(const ConvArgs &a, int v);
 
 #define EBS_DEFINE_TILED_KW(KWV, FSV)                                       \
     template <> int launch_tiled_kw<KWV, FSV>(const ConvArgs &a, int v)     \
@@ -682,6 +728,16 @@ template <int KW, int FS> int launch_tiled_req_kw(const ConvArgs &a, int v);
             case 2: return launch_bits_req<KWV, 2, FSV>(a, v);              \
             case 3: return launch_bits_req<KWV, 3, FSV>(a, v);              \
             case 4: return launch_bits_req<KWV, 4, FSV>(a, v);              \
+        }                                                                   \
+        return EBS_ERR_BITWIDTH;                                            \
+    }                                                                       \
+    template <> int launch_tiled_planes_kw<KWV, FSV>(const ConvArgs &a, int v) \
+    {                                                                       \
+        switch (a.ka) {                                                     \
+            case 1: return launch_bits_planes<KWV, 1, FSV>(a, v);           \
+            case 2: return launch_bits_planes<KWV, 2, FSV>(a, v);           \
+            case 3: return launch_bits_planes<KWV, 3, FSV>(a, v);           \
+            case 4: return launch_bits_planes<KWV, 4, FSV>(a, v);           \
         }                                                                   \
         return EBS_ERR_BITWIDTH;                                            \
     }

@@ -47,6 +47,12 @@ int launch_zero_border(uint32_t *packed, int N, int H, int W, int words_per_pos,
 // Returns EBS_ERR_UNSUPPORTED when the tiling cannot run this shape.
 int launch_conv_tiled(const ConvArgs &a, int variant);
 int launch_requant_tiled(const ConvArgs &a);
+// Two-stage form (Sec. 4.3): stage 1 writes the k_w*k_a partial-product planes where a.acc
+// points ([m*k_a + k][N*OH*OW][K], int32); stage 2 recombines them (Eq. 14) and applies scale/offset.
+int launch_planes_tiled(const ConvArgs &a);      // EBS_ERR_UNSUPPORTED when the tiling cannot run the shape
+int launch_planes_naive(const ConvArgs &a);
+int launch_pow2_depthwise(const int32_t *planes, long long plane_elems, int K, int kw, int ka, const float *scale,
+                          const float *offset, int per_channel, int32_t *acc, float *out, hipStream_t st);
 int conv_tiled_variant_count();
 const char *conv_tiled_variant_name(int variant);
 
