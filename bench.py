@@ -42,6 +42,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-mfma", action="store_true", help="skip the int8 matrix-core comparison timing")
     ap.add_argument("--no-requant", action="store_true", help="skip timing the fused re-quantising call")
+    ap.add_argument("--no-two-stage", action="store_true", help="skip timing the literal two-stage form")
     ap.add_argument("--only", default=None, metavar="LAYER,KW,KA",
                     help="restrict the workload to one case (layer index and bitwidths), e.g. 0,2,2")
     ap.add_argument("--traffic-pass", action="store_true",
@@ -348,6 +349,48 @@ def main():
             "vs_pack_plus_conv": round((conv_us_sum + pack_us_sum) / t_us, 3),
         }
 
+    # ---- NEXT row: the literal two-stage form (partial products through memory, then the depthwise
+    #      power-of-two recombination), timed on the same cases as the fused kernel
+    two_stage = None
+    if not args.no_two_stage:
+        max_planes = max(ebs.ebs_partial_products_bytes(c.layer.N, c.layer.H, c.layer.W, c.layer.K, c.layer.R, c.layer.S,
+                                                        c.layer.stride, c.layer.pad, c.k_w, c.k_a) for c in cases)
+        planes = torch.empty(max_planes // 4, dtype=torch.int32, device=dev)
+        s1_us = s2_us = 0.0
+        p_bytes = 0
+        for b, r in zip(bufs, table):
+            c, L = b.case, b.case.layer
+            f1 = lambda: ebs.ebs_binary_conv_planes(b.pa, b.pw, L.N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad,
+                                                    c.k_w, c.k_a, planes, stream)
+            f2 = lambda: ebs.ebs_pow2_depthwise(planes, L.N * L.OH * L.OW, L.K, c.k_w, c.k_a, b.scale, b.offset,
+                                                b.per_channel, b.acc, b.out, stream)
+            f1()
+            f2()
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+            ev[0].record(stream)
+            for _ in range(5):
+                f1()
+            ev[1].record(stream)
+            for _ in range(5):
+                f2()
+            ev[2].record(stream)
+            torch.cuda.synchronize()
+            u1 = ev[0].elapsed_time(ev[1]) * 1e3 / 5
+            u2 = ev[1].elapsed_time(ev[2]) * 1e3 / 5
+            r["stage1_us"], r["stage2_us"] = round(u1, 2), round(u2, 2)
+            s1_us += u1
+            s2_us += u2
+            p_bytes += L.N * L.OH * L.OW * L.K * c.k_w * c.k_a * 4
+        del planes
+        two_stage = {
+            "kernel": "ebs_binary_conv_planes + ebs_pow2_depthwise (comparison only: P goes through HBM)",
+            "binary_tops": round(conv_ops / (s1_us + s2_us) / 1e6, 1),
+            "stage1_binary_tops": round(conv_ops / s1_us / 1e6, 1),
+            "stage2_hbm_gbs": round((p_bytes + 8 * sum(c.layer.N * c.layer.OH * c.layer.OW * c.layer.K for c in cases)) / s2_us / 1e3, 1),
+            "partial_product_bytes_per_step": p_bytes,
+            "fused_speedup": round((s1_us + s2_us) / conv_us_sum, 3),
+        }
+
     traffic = read_traffic(args.workload)
     if traffic is not None:
         roofline["traffic"] = traffic
@@ -367,6 +410,8 @@ def main():
         out["mfma_i8_comparison"] = mfma
     if requant is not None:
         out["requant_epilogue"] = requant
+    if two_stage is not None:
+        out["two_stage_comparison"] = two_stage
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cases)
     cases_out = args.cases_out
