@@ -79,6 +79,9 @@ class Case:
 
 
 ALL_BITS = [(kw, ka) for kw in range(1, 5) for ka in range(1, 5)]
+# Pairs with a five-bit operand: the rest of the paper's search space {1, ..., 5} (Sec. 5).
+FIVE_BITS = [(5, ka) for ka in range(1, 6)] + [(kw, 5) for kw in range(1, 5)]
+PAPER_BITS = ALL_BITS + FIVE_BITS
 
 
 def _conv3(name, N, C, HW, K, stride=1):

@@ -26,7 +26,7 @@
  *  - Outputs are NHWC: acc[n][oh][ow][k] with
  *    OH = floor((H + 2*pad - R)/stride) + 1 and OW likewise; taps outside the
  *    image contribute zero (activation level 0 is the real value 0).
- *  - Bitwidths: 1 <= k_w, k_a <= 4.
+ *  - Bitwidths: 1 <= k_w, k_a <= 5 (the paper's search space, Sec. 5).
  *  - Packed buffers are opaque: their size comes from the *_bytes() calls and
  *    their content is only meaningful to ebs_mixed_conv2d of the same library
  *    version.
@@ -44,7 +44,7 @@ extern "C" {
 typedef enum {
     EBS_OK = 0,
     EBS_ERR_NULL = -1,        /* a required pointer is NULL                         */
-    EBS_ERR_BITWIDTH = -2,    /* k_w or k_a outside [1, 4]                          */
+    EBS_ERR_BITWIDTH = -2,    /* k_w or k_a outside [1, 5]                          */
     EBS_ERR_SHAPE = -3,       /* non-positive extent, empty output, pad >= filter,
                                  or a tensor with 2^31 or more elements            */
     EBS_ERR_ALIGN = -4,       /* a buffer is not 16-byte aligned                    */

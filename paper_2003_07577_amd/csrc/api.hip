@@ -17,7 +17,7 @@ hipError_t &last_hip_error()
 static const long long kMaxElems = (1LL << 31) - 1;
 
 static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
-static bool bits_ok(int b) { return b >= 1 && b <= 4; }
+static bool bits_ok(int b) { return b >= 1 && b <= kMaxBits; }
 
 static int check_act_shape(int N, int H, int W, int C)
 {
@@ -86,7 +86,7 @@ const char *ebs_status_string(int s)
     switch (s) {
         case EBS_OK: return "EBS_OK";
         case EBS_ERR_NULL: return "EBS_ERR_NULL: required pointer is null";
-        case EBS_ERR_BITWIDTH: return "EBS_ERR_BITWIDTH: bitwidth outside [1,4]";
+        case EBS_ERR_BITWIDTH: return "EBS_ERR_BITWIDTH: bitwidth outside [1,5]";
         case EBS_ERR_SHAPE: return "EBS_ERR_SHAPE: invalid or too large shape";
         case EBS_ERR_ALIGN: return "EBS_ERR_ALIGN: buffer not 16-byte aligned";
         case EBS_ERR_UNSUPPORTED: return "EBS_ERR_UNSUPPORTED: no kernel for this request";

@@ -105,7 +105,7 @@ bd_requant_naive(const uint32_t *__restrict__ act, const uint32_t *__restrict__ 
     long long tt = t / g.OW;
     int oh = (int)(tt % g.OH);
     long long n = tt / g.OH;
-    uint32_t planes[4] = {0u, 0u, 0u, 0u};
+    uint32_t planes[kMaxBits] = {};
     for (int c = 0; c < 32; ++c) {
         const int k = word * 32 + c;
         if (k >= g.K) break;
@@ -113,7 +113,7 @@ bd_requant_naive(const uint32_t *__restrict__ act, const uint32_t *__restrict__ 
         const int ci = per_channel ? k : 0;
         const uint32_t lv = requant_level(acc, scale[ci], offset ? offset[ci] : 0.0f, alpha, qs);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) planes[j] |= ((lv >> j) & 1u) << c;
+        for (int j = 0; j < kMaxBits; ++j) planes[j] |= ((lv >> j) & 1u) << c;
     }
     const long long pos = (n * (g.OH + 2 * kActBorder) + oh + kActBorder) * (g.OW + 2 * kActBorder) + ow + kActBorder;
     for (int j = 0; j < k_next; ++j) next[(pos * cwn + word) * k_next + j] = planes[j];
@@ -141,10 +141,11 @@ static int dispatch(const ConvArgs &a)
 {
 #define EBS_CASE(w, x) case (w) * 8 + (x): return launch<w, x>(a);
     switch (a.kw * 8 + a.ka) {
-        EBS_CASE(1, 1) EBS_CASE(1, 2) EBS_CASE(1, 3) EBS_CASE(1, 4)
-        EBS_CASE(2, 1) EBS_CASE(2, 2) EBS_CASE(2, 3) EBS_CASE(2, 4)
-        EBS_CASE(3, 1) EBS_CASE(3, 2) EBS_CASE(3, 3) EBS_CASE(3, 4)
-        EBS_CASE(4, 1) EBS_CASE(4, 2) EBS_CASE(4, 3) EBS_CASE(4, 4)
+        EBS_CASE(1, 1) EBS_CASE(1, 2) EBS_CASE(1, 3) EBS_CASE(1, 4) EBS_CASE(1, 5)
+        EBS_CASE(2, 1) EBS_CASE(2, 2) EBS_CASE(2, 3) EBS_CASE(2, 4) EBS_CASE(2, 5)
+        EBS_CASE(3, 1) EBS_CASE(3, 2) EBS_CASE(3, 3) EBS_CASE(3, 4) EBS_CASE(3, 5)
+        EBS_CASE(4, 1) EBS_CASE(4, 2) EBS_CASE(4, 3) EBS_CASE(4, 4) EBS_CASE(4, 5)
+        EBS_CASE(5, 1) EBS_CASE(5, 2) EBS_CASE(5, 3) EBS_CASE(5, 4) EBS_CASE(5, 5)
     }
 #undef EBS_CASE
     return EBS_ERR_BITWIDTH;

@@ -14,7 +14,7 @@ template <int KW, int FS> int launch_tiled_planes_kw(const ConvArgs &a, int v);
     template <> int launch_tiled_kw<kw, 3>(const ConvArgs &a, int v); \
     template <> int launch_tiled_req_kw<kw, 0>(const ConvArgs &a, int v); \
     template <> int launch_tiled_req_kw<kw, 3>(const ConvArgs &a, int v);
-EBS_DECL(1) EBS_DECL(2) EBS_DECL(3) EBS_DECL(4)
+EBS_DECL(1) EBS_DECL(2) EBS_DECL(3) EBS_DECL(4) EBS_DECL(5)
 #undef EBS_DECL
 
 // Order must match EBS_TILED_VARIANTS in conv_tiled_kernel.h.
@@ -40,6 +40,7 @@ static int run_fs(const ConvArgs &a, int v)
         case 2: return launch_tiled_kw<2, FS>(a, v);
         case 3: return launch_tiled_kw<3, FS>(a, v);
         case 4: return launch_tiled_kw<4, FS>(a, v);
+        case 5: return launch_tiled_kw<5, FS>(a, v);
     }
     return EBS_ERR_BITWIDTH;
 }
@@ -59,6 +60,7 @@ static int run_req_fs(const ConvArgs &a, int v)
         case 2: return launch_tiled_req_kw<2, FS>(a, v);
         case 3: return launch_tiled_req_kw<3, FS>(a, v);
         case 4: return launch_tiled_req_kw<4, FS>(a, v);
+        case 5: return launch_tiled_req_kw<5, FS>(a, v);
     }
     return EBS_ERR_BITWIDTH;
 }
@@ -71,6 +73,7 @@ static int run_planes_fs(const ConvArgs &a, int v)
         case 2: return launch_tiled_planes_kw<2, FS>(a, v);
         case 3: return launch_tiled_planes_kw<3, FS>(a, v);
         case 4: return launch_tiled_planes_kw<4, FS>(a, v);
+        case 5: return launch_tiled_planes_kw<5, FS>(a, v);
     }
     return EBS_ERR_BITWIDTH;
 }
@@ -92,7 +95,7 @@ static int ch_slot(int cw) { return cw % 4 == 0 ? 2 : (cw % 2 == 0 ? 0 : 1); }
 // Channels per wave of the (budget, shift classes) tiles; mirrors TileOf in the kernel header.
 static int kt_of(int budget, int ncls)
 {
-    static const int k64[7] = {16, 8, 8, 8, 4, 4, 4}, k32[7] = {16, 8, 8, 8, 4, 4, 4}, k16[7] = {16, 8, 4, 4, 4, 4, 4};
+    static const int k64[9] = {16, 8, 8, 8, 4, 4, 4, 4, 4}, k32[9] = {16, 8, 8, 8, 4, 4, 4, 4, 4}, k16[9] = {16, 8, 4, 4, 4, 4, 4, 4, 4};
     const int *t = budget == 64 ? k64 : budget == 32 ? k32 : k16;
     return t[ncls - 1];
 }

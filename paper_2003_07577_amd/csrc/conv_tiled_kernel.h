@@ -100,7 +100,7 @@ template <int KW, int KA, int PIX, int KT, int CH, int MODE>
 struct Cfg {
     static constexpr bool PLN = MODE == MODE_PL;     // keep the plane pairs apart (stage 1 of Sec. 4.3 only)
     static constexpr int NCLS = PLN ? KW * KA : KW + KA - 1;     // accumulators per output
-    static constexpr int KAP = (KA == 3) ? 4 : KA;   // planes per staged word, padded to a power of two
+    static constexpr int KAP = (KA == 3) ? 4 : (KA == 5 ? 8 : KA);   // dwords per staged word: planes padded to a power of two
     static constexpr int WAVES = 4;
     static constexpr int WPX = MODE == MODE_P4 ? 4 : 1;          // waves along the position axis
     static constexpr int WK = (MODE == MODE_K4 || PLN) ? 4 : 1;           // waves along the channel axis
@@ -188,15 +188,23 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
             const int u = x / CH;
             const int w = x - u * CH;
             const uint32_t *src = act + (src0 + ((unsigned)u * sh.cw + w) * KA);
-            typedef typename UVec<C::KAP>::type vec_t;
-            vec_t vv;
-            if constexpr (C::KAP == 1) {
-                vv = src[0];
+            uint32_t *dst = lds + (w * sh.ucap + u) * C::KAP;
+            if constexpr (KA == 5) {
+                // five planes in an eight-dword slot: a 16-byte piece and a single word (the rest is never read)
+                const UVec<4>::type v4 = {src[0], src[1], src[2], src[3]};
+                *reinterpret_cast<UVec<4>::type *>(dst) = v4;
+                dst[4] = src[4];
             } else {
+                typedef typename UVec<C::KAP>::type vec_t;
+                vec_t vv;
+                if constexpr (C::KAP == 1) {
+                    vv = src[0];
+                } else {
 #pragma unroll
-                for (int j = 0; j < C::KAP; ++j) vv[j] = j < KA ? src[j] : 0u;
+                    for (int j = 0; j < C::KAP; ++j) vv[j] = j < KA ? src[j] : 0u;
+                }
+                *reinterpret_cast<vec_t *>(dst) = vv;
             }
-            *reinterpret_cast<vec_t *>(lds + (w * sh.ucap + u) * C::KAP) = vv;
         }
     };
 
@@ -250,13 +258,20 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
                     for (int i = 0; i < KW; ++i) q[g * kWgtGroup + c][i] = wg[g][qoff + c * KW + i];
         };
         auto load_x = [&](int idx, uint32_t (&x)[KA]) {          // idx: LDS dword index
-            typedef typename UVec<C::KAP>::type vec_t;
-            const vec_t v = *reinterpret_cast<const vec_t *>(lds + idx);
-            if constexpr (C::KAP == 1) {
-                x[0] = v;
-            } else {
+            if constexpr (KA == 5) {
+                const UVec<4>::type v = *reinterpret_cast<const UVec<4>::type *>(lds + idx);
 #pragma unroll
-                for (int j = 0; j < KA; ++j) x[j] = v[j];
+                for (int j = 0; j < 4; ++j) x[j] = v[j];
+                x[4] = lds[idx + 4];
+            } else {
+                typedef typename UVec<C::KAP>::type vec_t;
+                const vec_t v = *reinterpret_cast<const vec_t *>(lds + idx);
+                if constexpr (C::KAP == 1) {
+                    x[0] = v;
+                } else {
+#pragma unroll
+                    for (int j = 0; j < KA; ++j) x[j] = v[j];
+                }
             }
         };
         // Eq. 2 / Eq. 13 on one reduction word: AND + accumulating bitcount per plane pair
@@ -544,15 +559,15 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
 template <int BUDGET, int NCLS> struct TileOf;
 #define EBS_TILE(b, n, p, k) template <> struct TileOf<b, n> { static constexpr int PIX = p, KT = k; };
 EBS_TILE(64, 1, 4, 16)  EBS_TILE(64, 2, 4, 8)   EBS_TILE(64, 3, 2, 8)  EBS_TILE(64, 4, 2, 8)
-EBS_TILE(64, 5, 2, 4)   EBS_TILE(64, 6, 2, 4)   EBS_TILE(64, 7, 2, 4)
+EBS_TILE(64, 5, 2, 4)   EBS_TILE(64, 6, 2, 4)   EBS_TILE(64, 7, 2, 4)   EBS_TILE(64, 8, 2, 4)  EBS_TILE(64, 9, 2, 4)
 EBS_TILE(32, 1, 2, 16)  EBS_TILE(32, 2, 2, 8)   EBS_TILE(32, 3, 1, 8)  EBS_TILE(32, 4, 1, 8)
-EBS_TILE(32, 5, 1, 4)   EBS_TILE(32, 6, 1, 4)   EBS_TILE(32, 7, 1, 4)
+EBS_TILE(32, 5, 1, 4)   EBS_TILE(32, 6, 1, 4)   EBS_TILE(32, 7, 1, 4)   EBS_TILE(32, 8, 1, 4)  EBS_TILE(32, 9, 1, 4)
 EBS_TILE(16, 1, 1, 16)  EBS_TILE(16, 2, 1, 8)   EBS_TILE(16, 3, 1, 4)  EBS_TILE(16, 4, 1, 4)
-EBS_TILE(16, 5, 1, 4)   EBS_TILE(16, 6, 1, 4)   EBS_TILE(16, 7, 1, 4)
+EBS_TILE(16, 5, 1, 4)   EBS_TILE(16, 6, 1, 4)   EBS_TILE(16, 7, 1, 4)   EBS_TILE(16, 8, 1, 4)  EBS_TILE(16, 9, 1, 4)
 // budget 8: tiles of the re-quantising kernels (>= 8 channels per wave, so that the four waves of a
 // work-group hold whole 32-channel words of the next layer's packed activations)
 EBS_TILE(8, 1, 1, 16)   EBS_TILE(8, 2, 1, 8)    EBS_TILE(8, 3, 1, 8)   EBS_TILE(8, 4, 1, 8)
-EBS_TILE(8, 5, 1, 8)    EBS_TILE(8, 6, 1, 8)    EBS_TILE(8, 7, 1, 8)
+EBS_TILE(8, 5, 1, 8)    EBS_TILE(8, 6, 1, 8)    EBS_TILE(8, 7, 1, 8)    EBS_TILE(8, 8, 1, 8)   EBS_TILE(8, 9, 1, 8)
 #undef EBS_TILE
 
 // Tile of a (budget, k_w, k_a) kernel.  Budget 4 is the plane-pair kernel (MODE_PL): one
@@ -664,12 +679,25 @@ static int launch_bits(const ConvArgs &a, int v)
         }
         return EBS_ERR_UNSUPPORTED;
     }
-    switch (v) {
+    if constexpr (KW == 5 || KA == 5) {
+        // five-bit operands (the top of the paper's search space): the heuristic's variants only
+        switch (v) {
 #define EBS_X(idx, b, ch, mode) case idx: return launch_cfg<KW, KA, b, ch, mode, FS>(a);
-        EBS_TILED_VARIANTS(EBS_X)
+            EBS_X(3, 32, 2, MODE_P4)   EBS_X(4, 32, 1, MODE_P4)   EBS_X(5, 32, 4, MODE_P4)
+            EBS_X(9, 32, 2, MODE_K4)   EBS_X(10, 32, 1, MODE_K4)  EBS_X(11, 32, 4, MODE_K4)
+            EBS_X(12, 16, 2, MODE_K4)  EBS_X(13, 16, 1, MODE_K4)  EBS_X(14, 16, 4, MODE_K4)
+            EBS_X(17, 16, 4, MODE_R4)
 #undef EBS_X
+        }
+        return EBS_ERR_UNSUPPORTED;
+    } else {
+        switch (v) {
+#define EBS_X(idx, b, ch, mode) case idx: return launch_cfg<KW, KA, b, ch, mode, FS>(a);
+            EBS_TILED_VARIANTS(EBS_X)
+#undef EBS_X
+        }
+        return EBS_ERR_UNSUPPORTED;
     }
-    return EBS_ERR_UNSUPPORTED;
 }
 
 // Re-quantising kernels: K4 arrangement, chunk sizes 2 / 1 / 4 (variant 0 / 1 / 2).
@@ -718,6 +746,7 @@ template <int KW, int FS> int launch_tiled_planes_kw(const ConvArgs &a, int v);
             case 2: return launch_bits<KWV, 2, FSV>(a, v);                  \
             case 3: return launch_bits<KWV, 3, FSV>(a, v);                  \
             case 4: return launch_bits<KWV, 4, FSV>(a, v);                  \
+            case 5: return launch_bits<KWV, 5, FSV>(a, v);                  \
         }                                                                   \
         return EBS_ERR_BITWIDTH;                                            \
     }                                                                       \
@@ -728,6 +757,7 @@ template <int KW, int FS> int launch_tiled_planes_kw(const ConvArgs &a, int v);
             case 2: return launch_bits_req<KWV, 2, FSV>(a, v);              \
             case 3: return launch_bits_req<KWV, 3, FSV>(a, v);              \
             case 4: return launch_bits_req<KWV, 4, FSV>(a, v);              \
+            case 5: return launch_bits_req<KWV, 5, FSV>(a, v);              \
         }                                                                   \
         return EBS_ERR_BITWIDTH;                                            \
     }                                                                       \
@@ -738,6 +768,7 @@ template <int KW, int FS> int launch_tiled_planes_kw(const ConvArgs &a, int v);
             case 2: return launch_bits_planes<KWV, 2, FSV>(a, v);           \
             case 3: return launch_bits_planes<KWV, 3, FSV>(a, v);           \
             case 4: return launch_bits_planes<KWV, 4, FSV>(a, v);           \
+            case 5: return launch_bits_planes<KWV, 5, FSV>(a, v);           \
         }                                                                   \
         return EBS_ERR_BITWIDTH;                                            \
     }

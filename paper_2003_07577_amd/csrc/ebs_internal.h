@@ -11,6 +11,10 @@ namespace ebs {
 // a channel tile is one contiguous run of words (see pack.hip).
 constexpr int kWgtGroup = 16;
 
+// Largest bitwidth of weights and activations: the search space of the paper is {1, ..., 5}
+// (Sec. 5, implementation details).
+constexpr int kMaxBits = 5;
+
 struct ConvArgs {
     const uint32_t *act;   // packed activations  [N][H+2][W+2][cw][k_a], zero border of one position
     const uint32_t *wgt;   // packed weights      [ceil(K/16)][R*S][cw][16][k_w]

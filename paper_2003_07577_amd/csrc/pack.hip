@@ -86,6 +86,16 @@ __device__ __forceinline__ void planes_of_32(const uint32_t (&d)[8], uint32_t (&
     plane[3] = __builtin_amdgcn_perm(hi23, hi01, 0x07060302u);
 }
 
+// Digit 4 of the same 32 levels: bit 4 of byte r of d[i] is channel 4i+r.  The multiply gathers the
+// four bits (at 0, 8, 16, 24 after the shift and mask) into bits 24..27; no two partial products meet.
+__device__ __forceinline__ uint32_t fifth_plane_of_32(const uint32_t (&d)[8])
+{
+    uint32_t p = 0u;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) p |= ((((d[i] >> 4) & 0x01010101u) * 0x01020408u) >> 24 & 0xFu) << (4 * i);
+    return p;
+}
+
 template <int BITS>
 __global__ void __launch_bounds__(256)
 pack_act_c32(const uint8_t *__restrict__ levels, uint32_t *__restrict__ packed,
@@ -100,12 +110,16 @@ pack_act_c32(const uint8_t *__restrict__ levels, uint32_t *__restrict__ packed,
     const int hp = (int)fd_div((uint32_t)pos, div_wp);
     const int wp = pos - hp * Wp;
     const int h = hp - kActBorder, w = wp - kActBorder;
-    uint32_t plane[4] = {0u, 0u, 0u, 0u};
+    uint32_t plane[5] = {0u, 0u, 0u, 0u, 0u};
     if (h >= 0 && h < H && w >= 0 && w < W) {
         const uint4 *src = reinterpret_cast<const uint4 *>(levels + (((size_t)n * H + h) * W + w) * C + word * 32);
         const uint4 a = src[0], b = src[1];
         const uint32_t d[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-        planes_of_32(d, plane);
+        uint32_t low[4];
+        planes_of_32(d, low);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) plane[j] = low[j];
+        if (BITS == 5) plane[4] = fifth_plane_of_32(d);
     }
     uint32_t *dst = packed + ((size_t)n * items_per_image + item) * BITS;
 #pragma unroll
@@ -191,6 +205,7 @@ int pack_activations(const uint8_t *levels, uint32_t *packed, int N, int H, int 
         case 2: return launch_pack_act<2>(levels, packed, N, H, W, C, st);
         case 3: return launch_pack_act<3>(levels, packed, N, H, W, C, st);
         case 4: return launch_pack_act<4>(levels, packed, N, H, W, C, st);
+        case 5: return launch_pack_act<5>(levels, packed, N, H, W, C, st);
     }
     return EBS_ERR_BITWIDTH;
 }
@@ -202,6 +217,7 @@ int pack_weights(const uint8_t *levels, uint32_t *packed, int K, int C, int RS, 
         case 2: return launch_pack_wgt<2>(levels, packed, K, C, RS, st);
         case 3: return launch_pack_wgt<3>(levels, packed, K, C, RS, st);
         case 4: return launch_pack_wgt<4>(levels, packed, K, C, RS, st);
+        case 5: return launch_pack_wgt<5>(levels, packed, K, C, RS, st);
     }
     return EBS_ERR_BITWIDTH;
 }

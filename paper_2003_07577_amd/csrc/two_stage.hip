@@ -143,8 +143,9 @@ static int launch_depthwise(const int32_t *planes, long long elems, int K, const
 }
 
 #define EBS_ALL_PAIRS(X) \
-    X(1, 1) X(1, 2) X(1, 3) X(1, 4) X(2, 1) X(2, 2) X(2, 3) X(2, 4) \
-    X(3, 1) X(3, 2) X(3, 3) X(3, 4) X(4, 1) X(4, 2) X(4, 3) X(4, 4)
+    X(1, 1) X(1, 2) X(1, 3) X(1, 4) X(1, 5) X(2, 1) X(2, 2) X(2, 3) X(2, 4) X(2, 5) \
+    X(3, 1) X(3, 2) X(3, 3) X(3, 4) X(3, 5) X(4, 1) X(4, 2) X(4, 3) X(4, 4) X(4, 5) \
+    X(5, 1) X(5, 2) X(5, 3) X(5, 4) X(5, 5)
 
 int launch_planes_naive(const ConvArgs &a)
 {

@@ -49,7 +49,7 @@ def test_packed_sizes(lib):
     # weights: K rounded up to 16
     assert ebs.ebs_packed_weights_bytes(64, 64, 3, 3, 1) == 64 * 9 * 2 * 4
     assert ebs.ebs_packed_weights_bytes(1000, 2048, 1, 1, 4) == 1008 * 64 * 4 * 4
-    for bad in [(0, 8, 8, 16, 2), (1, 8, 8, 16, 0), (1, 8, 8, 16, 5), (1, -1, 8, 16, 2)]:
+    for bad in [(0, 8, 8, 16, 2), (1, 8, 8, 16, 0), (1, 8, 8, 16, 6), (1, -1, 8, 16, 2)]:
         assert ebs.ebs_packed_activations_bytes(*bad) == 0
     assert ebs.ebs_packed_weights_bytes(16, 16, 3, 3, 9) == 0
     assert ebs.ebs_packed_weights_bytes(16, 0, 3, 3, 2) == 0
@@ -70,7 +70,7 @@ def test_conv_argument_errors(lib):
     assert _conv(packed_wgt=None) == E["NULL"]
     assert _conv(scale=None) == E["NULL"]
     assert _conv(acc_out=None) == E["NULL"]
-    for k in (0, 5, -1):
+    for k in (0, 6, -1):
         assert _conv(k_w=k) == E["BITS"]
         assert _conv(k_a=k) == E["BITS"]
     for bad in [dict(N=0), dict(C=0), dict(H=-2), dict(W=0), dict(K=0), dict(R=0), dict(S=0),
@@ -130,7 +130,7 @@ def test_requant_argument_errors(lib):
                                             d["alpha"], d["kn"], d["nxt"], None, check=False)
     assert call(nxt=None) == -1
     assert call(pa=None) == -1
-    assert call(kn=0) == -2 and call(kn=5) == -2
+    assert call(kn=0) == -2 and call(kn=6) == -2
     assert call(kw=7) == -2
     assert call(alpha=0.0) == -3 and call(alpha=-1.0) == -3 and call(alpha=float("inf")) == -3
     assert call(alpha=float("nan")) == -3

@@ -11,7 +11,7 @@ from gpu_harness import (POISON, assert_f32_close, conv, pack, run_case, unpack_
 
 pytestmark = pytest.mark.gpu
 
-BITS = wl.ALL_BITS
+BITS = wl.PAPER_BITS
 
 
 def _check(oracle_mod, inp, k_w, k_a, stride, pad, variant=0, tag=""):
@@ -43,7 +43,7 @@ def test_config1_tiny(oracle_mod):
 
 # ------------------------------------------------------------------ packing
 @pytest.mark.parametrize("C", [16, 32, 48, 64, 100, 1000])
-@pytest.mark.parametrize("bits", [1, 2, 3, 4])
+@pytest.mark.parametrize("bits", [1, 2, 3, 4, 5])
 def test_pack_roundtrip(C, bits):
     import torch
     rng = np.random.default_rng(C * 10 + bits)

@@ -49,7 +49,7 @@ GEOS = [  # N, C, H, W, K, R, S, stride, pad
 ]
 
 
-@pytest.mark.parametrize("kw,ka", [(1, 1), (1, 3), (2, 2), (3, 4), (4, 1), (4, 4)])
+@pytest.mark.parametrize("kw,ka", [(1, 1), (1, 3), (2, 2), (3, 4), (4, 1), (4, 4), (5, 5), (2, 5), (5, 1)])
 def test_requant_levels_match_oracle(oracle_mod, kw, ka):
     for gi, (N, C, H, W, K, R, S, st, pad) in enumerate(GEOS):
         inp = wl.random_case(7000 + 10 * gi + kw * 4 + ka, N, C, H, W, K, R, S, st, pad, kw, ka,
@@ -58,7 +58,7 @@ def test_requant_levels_match_oracle(oracle_mod, kw, ka):
         top = C * R * S * (2 ** kw - 1) * (2 ** ka - 1)
         inp["scale"] = (inp["scale"] * np.float32(60.0 / top)).astype(np.float32)
         inp["offset"] = (inp["offset"] * np.float32(10.0) - np.float32(0.5)).astype(np.float32)
-        for alpha, k_next in [(6.0, 1 + (gi + kw) % 4), (2.37, 1 + (gi + ka + 1) % 4)]:
+        for alpha, k_next in [(6.0, 1 + (gi + kw) % 5), (2.37, 1 + (gi + ka + 1) % 5)]:
             _check(oracle_mod, inp, kw, ka, st, pad, alpha, k_next, f"geo{gi}")
 
 

@@ -20,7 +20,7 @@ GEOS = [  # N, C, H, W, K, R, S, stride, pad
 ]
 
 
-@pytest.mark.parametrize("kw,ka", wl.ALL_BITS)
+@pytest.mark.parametrize("kw,ka", wl.PAPER_BITS)
 def test_signed_accumulators_match_oracle(oracle_mod, kw, ka):
     import torch
     for gi, (N, C, H, W, K, R, S, st, pad) in enumerate(GEOS):

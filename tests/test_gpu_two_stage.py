@@ -39,7 +39,7 @@ def _two_stage(d, kw, ka, st, pad):
     return planes.cpu().numpy().reshape(kw, ka, g["N"], g["OH"], g["OW"], g["K"])
 
 
-@pytest.mark.parametrize("kw,ka", wl.ALL_BITS)
+@pytest.mark.parametrize("kw,ka", wl.PAPER_BITS)
 def test_two_stage_matches_oracle(oracle_mod, kw, ka):
     for gi, (N, C, H, W, K, R, S, st, pad) in enumerate(GEOS):
         inp = wl.random_case(7300 + 20 * gi + 4 * kw + ka, N, C, H, W, K, R, S, st, pad, kw, ka,
@@ -62,7 +62,7 @@ def test_two_stage_matches_oracle(oracle_mod, kw, ka):
         assert_f32_close(d["out"].cpu().numpy(), fref, ref, inp["scale"], inp["per_channel"])
 
 
-@pytest.mark.parametrize("kw,ka,positions,K", [(2, 3, 37, 5), (4, 4, 64, 32), (1, 1, 3, 1), (3, 2, 1000, 12), (4, 1, 129, 7)])
+@pytest.mark.parametrize("kw,ka,positions,K", [(2, 3, 37, 5), (4, 4, 64, 32), (1, 1, 3, 1), (3, 2, 1000, 12), (4, 1, 129, 7), (5, 5, 50, 6), (2, 5, 31, 3)])
 def test_depthwise_stage_alone_on_arbitrary_planes(oracle_mod, kw, ka, positions, K):
     """Stage 2 does not depend on where P came from: random int32 planes (values as large as a
     C*R*S = 4608 reduction gives), vector and scalar paths, per-channel scales."""
@@ -121,10 +121,10 @@ def test_two_stage_argument_errors():
     buf = torch.zeros(1024, dtype=torch.int32, device=dev)
     sc = torch.ones(1, dtype=torch.float32, device=dev)
     assert ebs.ebs_pow2_depthwise(None, 4, 4, 2, 2, sc, None, False, buf, None, check=False) == -1
-    assert ebs.ebs_pow2_depthwise(buf, 4, 4, 5, 2, sc, None, False, buf, None, check=False) == -2
+    assert ebs.ebs_pow2_depthwise(buf, 4, 4, 6, 2, sc, None, False, buf, None, check=False) == -2
     assert ebs.ebs_pow2_depthwise(buf, 0, 4, 2, 2, sc, None, False, buf, None, check=False) == -3
     assert ebs.ebs_pow2_depthwise(buf.data_ptr() + 4, 4, 4, 2, 2, sc, None, False, buf, None, check=False) == -4
     assert ebs.ebs_binary_conv_planes(buf, buf, 1, 16, 8, 8, 16, 3, 3, 1, 1, 2, 2, None, check=False) == -1
     assert ebs.ebs_binary_conv_planes(buf, buf, 1, 16, 8, 8, 16, 3, 3, 1, 1, 0, 2, buf, check=False) == -2
-    assert ebs.ebs_partial_products_bytes(1, 8, 8, 16, 3, 3, 1, 1, 2, 5) == 0
+    assert ebs.ebs_partial_products_bytes(1, 8, 8, 16, 3, 3, 1, 1, 2, 6) == 0
     assert ebs.ebs_partial_products_bytes(1, 2, 2, 16, 5, 5, 1, 1, 2, 2) == 0

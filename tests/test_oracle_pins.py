@@ -10,7 +10,7 @@ import torch
 from ebs_workloads import draw_levels
 from golden_io import read_sections
 
-BITS = [(kw, ka) for kw in range(1, 5) for ka in range(1, 5)]
+BITS = [(kw, ka) for kw in range(1, 6) for ka in range(1, 6)]     # the paper's search space {1..5} (Sec. 5)
 
 
 def _rand(seed, N, C, H, W, K, R, S, kw, ka):
@@ -75,7 +75,7 @@ def test_direct_equals_bitplane_bruteforce(oracle_mod, kw, ka):
         assert np.array_equal(d, b), (kw, ka, gi)
 
 
-@pytest.mark.parametrize("kw,ka", [(1, 1), (2, 3), (4, 4), (3, 1)])
+@pytest.mark.parametrize("kw,ka", [(1, 1), (2, 3), (4, 4), (3, 1), (5, 2), (5, 5)])
 def test_matrix_form_equals_direct(oracle_mod, kw, ka):
     N, C, H, W, K, R, S, st, pad = 2, 6, 5, 5, 3, 3, 3, 2, 1
     a, q = _rand(77 + kw * 5 + ka, N, C, H, W, K, R, S, kw, ka)
@@ -120,7 +120,7 @@ def test_1x1_is_integer_matmul(oracle_mod):
 
 
 # ---------------------------------------------------------------- closed forms
-@pytest.mark.parametrize("kw,ka", [(1, 1), (2, 2), (4, 3), (4, 4)])
+@pytest.mark.parametrize("kw,ka", [(1, 1), (2, 2), (4, 3), (4, 4), (5, 5), (1, 5)])
 def test_all_max_levels_closed_form(oracle_mod, kw, ka):
     N, C, H, W, K = 1, 12, 6, 7, 3
     top = (2 ** kw - 1) * (2 ** ka - 1)
@@ -285,7 +285,7 @@ def test_requant_hand_examples(oracle_mod):
         assert int(got[0, 0]) == int(exp), (bits, alpha, scale, offset, acc, exp, int(got[0, 0]))
 
 
-@pytest.mark.parametrize("bits,alpha", [(2, 3.0), (4, 7.5), (3, 3.5), (1, 1.0), (4, 15.0)])
+@pytest.mark.parametrize("bits,alpha", [(2, 3.0), (4, 7.5), (3, 3.5), (1, 1.0), (4, 15.0), (5, 15.5), (5, 6.0)])
 def test_requant_matches_float64_formula_on_exact_inputs(oracle_mod, bits, alpha):
     """With (2^b-1)/alpha an integer and power-of-two scales, every intermediate is exact in
     single precision, so the float64 textbook formula must give the same levels."""
@@ -323,7 +323,7 @@ def test_requant_per_channel_and_general_inputs_close_to_float64(oracle_mod):
 
 
 # ---------------------------------------------------------------- signed weights (Eq. 1a)
-@pytest.mark.parametrize("kw,ka", [(1, 1), (1, 4), (2, 2), (3, 2), (4, 4)])
+@pytest.mark.parametrize("kw,ka", [(1, 1), (1, 4), (2, 2), (3, 2), (4, 4), (5, 3), (2, 5)])
 def test_signed_conv_against_library_and_identity(oracle_mod, kw, ka):
     N, C, H, W, K, R, S, st, pad = 2, 21, 7, 6, 5, 3, 3, 2, 1
     a, q = _rand(300 + kw * 4 + ka, N, C, H, W, K, R, S, kw, ka)
@@ -392,7 +392,7 @@ def test_depthwise_stage_is_lambda_products(oracle_mod):
     assert np.array_equal(oracle_mod.depthwise_pow2(P, M, Kb), Lw @ P @ Lx.T)
 
 
-@pytest.mark.parametrize("kw,ka", [(1, 1), (2, 3), (4, 4), (3, 1), (1, 4)])
+@pytest.mark.parametrize("kw,ka", [(1, 1), (2, 3), (4, 4), (3, 1), (1, 4), (5, 5), (3, 5)])
 def test_partial_products_match_bitwise_and_matrix_forms(oracle_mod, kw, ka):
     N, C, H, W, K, R, S, st, pad = 2, 7, 6, 5, 5, 3, 2, 2, 1
     a, q = _rand(500 + kw * 5 + ka, N, C, H, W, K, R, S, kw, ka)
