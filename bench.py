@@ -29,7 +29,7 @@ ALU_LANE_OPS = 256 * 64 * 2.4e9
 PEAK_BINARY_TOPS = ALU_LANE_OPS / 2 * 64 / 1e12      # 1258.3
 HBM_PEAK_GBS = 8000.0
 
-WORKLOADS = {"tiny": 1, "cifar20": 2, "resnet18": 3, "resnet50": 4, "fc": 5}
+WORKLOADS = {"tiny": 1, "cifar20": 2, "resnet18": 3, "resnet50": 4, "fc": 5, "resnet18_five": 6}
 
 
 def parse():

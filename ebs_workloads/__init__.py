@@ -60,7 +60,10 @@ class Case:
 
     @property
     def seed(self) -> int:
-        return BASE_SEED + 100000 * self.config + 100 * self.layer_index + 4 * (self.k_w - 1) + (self.k_a - 1)
+        pair = 4 * (self.k_w - 1) + (self.k_a - 1)
+        if self.k_w > 4 or self.k_a > 4:            # five-bit pairs: numbered after the sixteen pairs of {1..4}^2
+            pair = 16 + 5 * (self.k_w - 1) + (self.k_a - 1)
+        return BASE_SEED + 100000 * self.config + 100 * self.layer_index + pair
 
     @property
     def binary_ops(self) -> int:
@@ -124,7 +127,7 @@ def resnet50_layers(N: int = 64) -> List[Layer]:
 
 
 def config_cases(config: int, N: Optional[int] = None) -> List[Case]:
-    """Cases of workload family `config` (1..5); N overrides the batch size."""
+    """Cases of workload family `config` (1..6); N overrides the batch size."""
     cases: List[Case] = []
     if config == 1:
         cases.append(Case(1, 0, _conv3("tiny", N or 1, 16, 8, 16), 2, 2))
@@ -145,8 +148,13 @@ def config_cases(config: int, N: Optional[int] = None) -> List[Case]:
         L = _conv1("fc2048->1000", N or 1024, 2048, 1, 1000)
         for kw, ka in [(4, 4), (1, 1)]:
             cases.append(Case(5, 0, L, kw, ka, "uniform", "channel"))
+    elif config == 6:
+        # the ResNet-18-shaped layers of config 3 at the pairs with a five-bit operand
+        for i, L in enumerate(resnet18_layers(N or 64)):
+            for kw, ka in FIVE_BITS:
+                cases.append(Case(6, i, L, kw, ka, "halfnormal", "layer_const"))
     else:
-        raise ValueError("config must be 1..5")
+        raise ValueError("config must be 1..6")
     return cases
 
 

@@ -92,12 +92,13 @@ int launch_planes_tiled(const ConvArgs &a)
 // Slot of the chunk size inside a family of three: order ch2, ch1, ch4.
 static int ch_slot(int cw) { return cw % 4 == 0 ? 2 : (cw % 2 == 0 ? 0 : 1); }
 
-// Channels per wave of the (budget, shift classes) tiles; mirrors TileOf in the kernel header.
-static int kt_of(int budget, int ncls)
+// Channels per wave of the (budget, bitwidths) tiles; mirrors TileOf / TileSel in the kernel header.
+static int kt_of(int budget, int kw, int ka)
 {
     static const int k64[9] = {16, 8, 8, 8, 4, 4, 4, 4, 4}, k32[9] = {16, 8, 8, 8, 4, 4, 4, 4, 4}, k16[9] = {16, 8, 4, 4, 4, 4, 4, 4, 4};
+    if (ka == 5 && budget != 64) return kw <= 3 ? 8 : 4;
     const int *t = budget == 64 ? k64 : budget == 32 ? k32 : k16;
-    return t[ncls - 1];
+    return t[kw + ka - 2];
 }
 
 // Fused re-quantisation: the K4 kernels whose work-groups own whole 32-channel words.
@@ -130,8 +131,8 @@ int launch_conv_tiled(const ConvArgs &a, int variant)
     int order[6];
     int n = 0;
     if (rs > 1 && rs * a.cw >= 64 && positions <= 16384 && a.cw % 4 == 0) order[n++] = V_R4_16;
-    if (a.K >= 4 * kt_of(budget, ncls)) order[n++] = (budget == 16 ? V_K4_16 : V_K4_32) + slot;
-    else if (a.K >= 4 * kt_of(16, ncls)) order[n++] = V_K4_16 + slot;
+    if (a.K >= 4 * kt_of(budget, a.kw, a.ka)) order[n++] = (budget == 16 ? V_K4_16 : V_K4_32) + slot;
+    else if (a.K >= 4 * kt_of(16, a.kw, a.ka)) order[n++] = V_K4_16 + slot;
     order[n++] = V_P4_32 + slot;
     order[n++] = V_P4_32 + 1;       // ch1: smallest staging footprint
     for (int i = 0; i < n; ++i) {

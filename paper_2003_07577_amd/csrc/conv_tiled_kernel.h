@@ -100,7 +100,12 @@ template <int KW, int KA, int PIX, int KT, int CH, int MODE>
 struct Cfg {
     static constexpr bool PLN = MODE == MODE_PL;     // keep the plane pairs apart (stage 1 of Sec. 4.3 only)
     static constexpr int NCLS = PLN ? KW * KA : KW + KA - 1;     // accumulators per output
-    static constexpr int KAP = (KA == 3) ? 4 : (KA == 5 ? 8 : KA);   // dwords per staged word: planes padded to a power of two
+    // Staged planes per (position, word): padded to a power of two so that one LDS access fetches
+    // them.  The fifth plane of five-bit activations lives in a second region, [word][position],
+    // behind the four-plane one (a single eight-dword slot would put the lanes of a wave on one
+    // bank in eight).
+    static constexpr int KAP = (KA == 3 || KA == 5) ? 4 : KA;
+    static constexpr int XTRA = KA == 5 ? 1 : 0;
     static constexpr int WAVES = 4;
     static constexpr int WPX = MODE == MODE_P4 ? 4 : 1;          // waves along the position axis
     static constexpr int WK = (MODE == MODE_K4 || PLN) ? 4 : 1;           // waves along the channel axis
@@ -108,7 +113,7 @@ struct Cfg {
     static constexpr int TPW = 64 * PIX;             // positions per wave
     static constexpr int TP = WPX * TPW;             // positions per work-group
     static constexpr int KB = WK * KT;               // channels per work-group
-    static constexpr int POSW = CH * KAP;            // LDS dwords per staged position (all words of the chunk)
+    static constexpr int POSW = CH * (KAP + XTRA);   // LDS dwords per staged position (all words of the chunk)
     static constexpr int WSTEP = CH / WRED;          // reduction words per wave per tap per chunk
     static constexpr int WPS = (NCLS <= 2 && WSTEP % 2 == 0) ? 2 : 1;   // words per pipelined step (3x3 path)
     static constexpr int KG = (KT + kWgtGroup - 1) / kWgtGroup;   // 16-channel weight groups per tile
@@ -179,6 +184,9 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
         my_lds[p] = (base_of(tc) - u_lo) * C::KAP;
     }
 
+    const int xtra_base = sh.ucap * CH * C::KAP;      // start of the fifth-plane region (five-bit activations)
+    (void)xtra_base;
+
     // ---- staging of one reduction chunk: positions [u_lo, u_hi] of the bordered
     //      input are contiguous in memory; copy CH words (x KA planes) of each
     const int n_stage = (u_hi - u_lo + 1) * CH;
@@ -190,10 +198,9 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
             const uint32_t *src = act + (src0 + ((unsigned)u * sh.cw + w) * KA);
             uint32_t *dst = lds + (w * sh.ucap + u) * C::KAP;
             if constexpr (KA == 5) {
-                // five planes in an eight-dword slot: a 16-byte piece and a single word (the rest is never read)
                 const UVec<4>::type v4 = {src[0], src[1], src[2], src[3]};
                 *reinterpret_cast<UVec<4>::type *>(dst) = v4;
-                dst[4] = src[4];
+                lds[xtra_base + w * sh.ucap + u] = src[4];
             } else {
                 typedef typename UVec<C::KAP>::type vec_t;
                 vec_t vv;
@@ -262,7 +269,7 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
                 const UVec<4>::type v = *reinterpret_cast<const UVec<4>::type *>(lds + idx);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) x[j] = v[j];
-                x[4] = lds[idx + 4];
+                x[4] = lds[xtra_base + (idx >> 2)];
             } else {
                 typedef typename UVec<C::KAP>::type vec_t;
                 const vec_t v = *reinterpret_cast<const vec_t *>(lds + idx);
@@ -577,6 +584,18 @@ template <int BUDGET, int KW, int KA> struct TileSel {
     static constexpr int PIX = TileOf<BUDGET, KW + KA - 1>::PIX;
     static constexpr int KT = TileOf<BUDGET, KW + KA - 1>::KT;
 };
+// Five-bit activations with up to three weight bits: eight channels per wave (the shift-class table
+// above would give four; the weight words are few here, and more channels share each activation fetch).
+template <int KW> struct TileSelA5 {
+    static constexpr int PIX = 1;
+    static constexpr int KT = KW <= 3 ? 8 : 4;
+};
+template <> struct TileSel<16, 1, 5> : TileSelA5<1> {};
+template <> struct TileSel<16, 2, 5> : TileSelA5<2> {};
+template <> struct TileSel<16, 3, 5> : TileSelA5<3> {};
+template <> struct TileSel<32, 1, 5> : TileSelA5<1> {};
+template <> struct TileSel<32, 2, 5> : TileSelA5<2> {};
+template <> struct TileSel<32, 3, 5> : TileSelA5<3> {};
 template <int KW, int KA> struct TileSel<4, KW, KA> {
     static constexpr int PIX = 1;
     static constexpr int KT_ACC = KW * KA <= 4 ? 16 : (KW * KA <= 8 ? 8 : 4);

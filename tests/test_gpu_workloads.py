@@ -45,6 +45,11 @@ def test_config3_resnet18_layers_all_bit_pairs(oracle_mod, layer_index):
     _run_config(oracle_mod, 3, keep=lambda c: c.layer_index == layer_index)
 
 
+@pytest.mark.parametrize("layer_index", [0, 3, 5])
+def test_config6_resnet18_layers_five_bit_pairs(oracle_mod, layer_index):
+    _run_config(oracle_mod, 6, keep=lambda c: c.layer_index == layer_index)
+
+
 def test_config4_resnet50_bottlenecks(oracle_mod):
     _run_config(oracle_mod, 4)
 
