@@ -13,6 +13,9 @@ Two layers:
 * ``bd_matrix_form`` below (numpy): the paper's two-stage statement of binary
   decomposition in matrix notation (Sec. 4.3, Eq. 12-15), used on small cases.
 
+* ``quantizers.py`` (numpy, float64): the weight and activation quantisers (Eq. 1a-1c) and the
+  aggregated quantisation functions of the bitwidth search (Eq. 6, 7, 9).
+
 Parity status: every function here is pinned by ``tests/test_oracle_pins.py``
 (closed forms, brute force, float64 library convolution, integer matmul,
 hand-computed fixture).  Nothing is "parity unpinned".
@@ -60,6 +63,8 @@ def _load():
         lib.oracle_dequant.restype = None
         lib.oracle_requant_levels.argtypes = [i32p, ctypes.c_size_t, ci, f32p, f32p, ci, ctypes.c_float, ci, u8p]
         lib.oracle_requant_levels.restype = None
+        lib.oracle_activation_levels.argtypes = [f32p, ctypes.c_size_t, ctypes.c_float, ci, u8p]
+        lib.oracle_activation_levels.restype = None
         lib.oracle_num_threads.argtypes = []
         lib.oracle_num_threads.restype = ci
         _lib = lib
@@ -321,4 +326,10 @@ def depthwise_pow2(P, M, Kb):
             window = P[i * M:(i + 1) * M, j * Kb:(j + 1) * Kb]
             O[i, j] = int((window * kernel).sum())
     return O
+
+
+from .quantizers import (  # noqa: E402,F401
+    quantize_b, weight_levels, quantize_weights, activation_levels, quantize_activations,
+    quantize_activations_f64, softmax, gumbel_softmax, aggregate_weights, aggregate_activations,
+)
 

@@ -252,6 +252,21 @@ void oracle_requant_levels(const int32_t *acc, size_t n_pix, int K,
         }
 }
 
+/*
+ * Activation quantiser on real inputs (Eq. 1b-1c): clip to [0, alpha], normalise, round half up
+ * to b bits; returns the integer level (the quantised value is alpha*level/(2^b - 1)).  The
+ * rounding decides an integer, so precision and order are fixed as above (single precision):
+ *     z = min(max(x, 0), alpha);  qs = (float)(2^b - 1) / alpha;  level = floorf(fmaf(z, qs, 0.5f))
+ */
+void oracle_activation_levels(const float *x, size_t count, float alpha, int bits, uint8_t *levels)
+{
+    const float qs = (float)((1 << bits) - 1) / alpha;
+    for (size_t i = 0; i < count; ++i) {
+        float z = fminf(fmaxf(x[i], 0.0f), alpha);
+        levels[i] = (uint8_t)(int)floorf(fmaf(z, qs, 0.5f));
+    }
+}
+
 int oracle_num_threads(void)
 {
 #ifdef _OPENMP

@@ -410,3 +410,136 @@ def test_partial_products_match_bitwise_and_matrix_forms(oracle_mod, kw, ka):
     O2 = oracle_mod.depthwise_pow2(Pm, kw, ka)
     assert np.array_equal(O2.T.reshape(N, OH, OW, K), oracle_mod.conv2d_levels(a, q, st, pad))
 
+
+
+# ---------------------------------------------------------------- quantisers (Eq. 1a-1c) and aggregation (Eq. 6, 7, 9)
+def test_weight_quantiser_hand_fixture(oracle_mod):
+    g = read_sections("quantizer_examples.txt")
+    W = np.arctanh(g["tanh_tenths"][0] / 10.0)
+    for b in (1, 2, 3):
+        L = g[f"levels_b{b}"][0]
+        assert np.array_equal(oracle_mod.weight_levels(W, b), L)
+        assert np.allclose(oracle_mod.quantize_weights(W, b), 2.0 * L / (2 ** b - 1) - 1.0, atol=1e-15)
+    # the paper's aggregate example: B = {2, 3}, r = [0, 0] is 0.5 W^2 + 0.5 W^3
+    agg = oracle_mod.aggregate_weights(W, [2, 3], [0.0, 0.0])
+    assert np.allclose(agg, g["aggregate_b2_b3_equal_strengths_42nds"][0] / 42.0, atol=1e-15)
+    assert np.allclose(agg, 0.5 * oracle_mod.quantize_weights(W, 2) + 0.5 * oracle_mod.quantize_weights(W, 3), atol=1e-15)
+
+
+def test_quantize_b_rounds_half_up(oracle_mod):
+    # (2^b - 1) x exactly at .5: up, never to even
+    assert oracle_mod.quantize_b(1.0 / 6.0, 2) == pytest.approx(1.0 / 3.0)     # 0.5 -> 1 (to-even would give 0)
+    assert oracle_mod.quantize_b(0.5, 2) == pytest.approx(2.0 / 3.0)           # 1.5 -> 2
+    assert oracle_mod.quantize_b(2.5 / 7.0, 3) == pytest.approx(3.0 / 7.0)     # 2.5 -> 3 (to-even would give 2)
+    assert oracle_mod.quantize_b(0.0, 4) == 0.0 and oracle_mod.quantize_b(1.0, 4) == 1.0
+    x = np.linspace(0, 1, 1001)
+    for b in range(1, 6):
+        q = oracle_mod.quantize_b(x, b)
+        assert np.all(np.abs(q - x) <= 0.5 / (2 ** b - 1) + 1e-12)             # nearest level
+        assert len(np.unique(q)) == 2 ** b                                     # a uniform staircase of 2^b levels
+
+
+@pytest.mark.parametrize("b", [1, 2, 3, 4, 5])
+def test_weight_quantiser_properties(oracle_mod, b):
+    rng = np.random.default_rng(60 + b)
+    W = rng.normal(0, 0.7, (4, 3, 3, 5))
+    L = oracle_mod.weight_levels(W, b)
+    What = oracle_mod.quantize_weights(W, b)
+    n = 2 ** b - 1
+    assert L.min() >= 0 and L.max() <= n
+    assert np.allclose(What, 2.0 * L / n - 1.0, atol=1e-15)
+    # the largest |w| maps to an end of the range, and W_hat lies in [-1, 1]
+    i = np.unravel_index(np.argmax(np.abs(W)), W.shape)
+    assert What[i] == (1.0 if W[i] > 0 else -1.0)
+    assert What.min() >= -1.0 and What.max() <= 1.0
+    # monotone in w, and within half a step of the normalised tanh (Eq. 1a before rounding)
+    order = np.argsort(W.reshape(-1))
+    assert np.all(np.diff(L.reshape(-1)[order].astype(int)) >= 0)
+    t = np.tanh(W)
+    assert np.all(np.abs(What - t / np.abs(t).max()) <= 1.0 / n + 1e-12)
+    # invariant to a common sign flip up to the ties: levels mirror
+    Lneg = oracle_mod.weight_levels(-W, b)
+    assert np.mean(Lneg.astype(int) + L.astype(int) == n) > 0.999
+    if b == 1:
+        assert np.array_equal(What, np.where(W >= 0, 1.0, -1.0))               # one bit: the sign
+    # all-zero weights: defined (normalised value 1/2), no NaN
+    Z = oracle_mod.weight_levels(np.zeros(7), b)
+    assert np.all(Z == 2 ** (b - 1))
+
+
+def test_activation_levels_hand_examples_and_float64_definition(oracle_mod):
+    import os
+    from golden_io import GOLDEN
+    rows = [[float(v) for v in l.split()] for l in open(os.path.join(GOLDEN, "requant_examples.txt"))
+            if l.strip() and not l.startswith("#") and not l.startswith("[")]
+    for bits, alpha, scale, offset, acc, want in rows:
+        x = np.float32(scale) * np.float32(acc) + np.float32(offset)           # exact by construction of the fixture
+        assert int(oracle_mod.activation_levels([x], float(alpha), int(bits))[0]) == int(want)
+    # against Eq. 1b evaluated in float64 on inputs where single precision is exact (multiples of 1/64, alpha a power of two times n)
+    for b, alpha in [(1, 1.0), (2, 3.0), (3, 3.5), (4, 7.5), (5, 15.5)]:
+        x = (np.arange(-64, 1200) / 64.0).astype(np.float32)
+        L = oracle_mod.activation_levels(x, alpha, b)
+        ref = oracle_mod.quantize_activations_f64(x, alpha, b)
+        assert np.allclose(alpha * L / (2 ** b - 1), ref, atol=1e-12)
+        assert np.allclose(oracle_mod.quantize_activations(x, alpha, b), ref, atol=1e-12)
+        assert L[0] == 0 and L[-1] == 2 ** b - 1                               # ReLU side and clip side
+        assert np.all(np.diff(L.astype(int)) >= 0)
+        # idempotent: a quantised value quantises to itself
+        lv = np.arange(2 ** b)
+        again = oracle_mod.activation_levels((alpha * lv / (2 ** b - 1)).astype(np.float32), alpha, b)
+        assert np.array_equal(again, lv)
+
+
+def test_activation_levels_general_inputs_close_to_float64(oracle_mod):
+    rng = np.random.default_rng(5)
+    x = np.abs(rng.normal(0, 2.5, 20000)).astype(np.float32) - 0.3
+    for b, alpha in [(2, 6.0), (4, 2.37), (5, 6.0)]:
+        L = oracle_mod.activation_levels(x, alpha, b).astype(int)
+        n = 2 ** b - 1
+        ref = np.floor(n * np.clip(x.astype(np.float64), 0, alpha) / alpha + 0.5).astype(int)
+        diff = L != ref
+        assert diff.mean() < 1e-3                                              # only inputs within an ulp of a tie may differ
+        v = n * np.clip(x.astype(np.float64), 0, alpha) / alpha + 0.5
+        assert np.all(np.abs(v[diff] - np.round(v[diff])) < 1e-5) and np.all(np.abs(L - ref) <= 1)
+
+
+def test_softmax_and_gumbel_coefficients(oracle_mod):
+    p = oracle_mod.softmax([0.0, 0.0])
+    assert np.allclose(p, [0.5, 0.5])
+    p = oracle_mod.softmax([-1.0, 1.0])                                        # the paper's second example: close to the larger bitwidth
+    assert np.allclose(p, [1 / (1 + np.e ** 2), np.e ** 2 / (1 + np.e ** 2)]) and p[1] > 0.88
+    r = np.array([0.3, -1.2, 2.0, 0.0, 0.7])
+    p = oracle_mod.softmax(r)
+    assert abs(p.sum() - 1) < 1e-15 and np.argmax(p) == 2
+    assert np.allclose(oracle_mod.softmax(r + 100.0), p)                       # shift invariance (and no overflow)
+    # zero noise at tau = 1 is the plain softmax; small tau tends to the one-hot of argmax(log p + g)
+    assert np.allclose(oracle_mod.gumbel_softmax(r, np.zeros(5), 1.0), p)
+    gmb = np.array([0.1, 3.0, -0.5, 0.2, 0.0])
+    c = oracle_mod.gumbel_softmax(r, gmb, 0.01)
+    assert np.argmax(c) == np.argmax(np.log(p) + gmb) and c.max() > 0.999
+    c = oracle_mod.gumbel_softmax(r, gmb, 2.0)
+    y = (np.log(p) + gmb) / 2.0
+    assert np.allclose(c, np.exp(y) / np.exp(y).sum()) and abs(c.sum() - 1) < 1e-15
+
+
+def test_aggregates_reduce_to_single_quantisers(oracle_mod):
+    rng = np.random.default_rng(8)
+    W = rng.normal(0, 1, 300)
+    X = (np.abs(rng.normal(0, 2, 300)) - 0.2).astype(np.float32)
+    # one candidate, or one dominant strength (Eq. 5: the arg max), is the plain quantiser
+    assert np.allclose(oracle_mod.aggregate_weights(W, [3], [0.7]), oracle_mod.quantize_weights(W, 3))
+    assert np.allclose(oracle_mod.aggregate_weights(W, [1, 2, 3, 4, 5], [0, 0, 80.0, 0, 0]), oracle_mod.quantize_weights(W, 3), atol=1e-12)
+    assert np.allclose(oracle_mod.aggregate_activations(X, 6.0, [2, 4], [0.0, 90.0]), oracle_mod.quantize_activations(X, 6.0, 4), atol=1e-12)
+    # a convex combination: between the smallest and the largest candidate value
+    bits = [1, 2, 3, 4, 5]
+    r = rng.normal(0, 1, 5)
+    agg = oracle_mod.aggregate_weights(W, bits, r)
+    each = np.stack([oracle_mod.quantize_weights(W, b) for b in bits])
+    assert np.all(agg <= each.max(0) + 1e-12) and np.all(agg >= each.min(0) - 1e-12)
+    assert np.allclose(agg, (oracle_mod.softmax(r)[:, None] * each).sum(0))
+    aggx = oracle_mod.aggregate_activations(X, 6.0, bits, r, gumbel=np.zeros(5), tau=1.0)
+    eachx = np.stack([oracle_mod.quantize_activations(X, 6.0, b) for b in bits])
+    assert np.allclose(aggx, (oracle_mod.softmax(r)[:, None] * eachx).sum(0))
+    # linear in the coefficients: Eq. 7 = (sum_i a_i W^i) * (sum_j b_j X^j) needs only these two factors
+    assert np.allclose(oracle_mod.aggregate_weights(W, [2, 3], [0.0, 0.0]),
+                       0.5 * oracle_mod.quantize_weights(W, 2) + 0.5 * oracle_mod.quantize_weights(W, 3))
