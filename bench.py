@@ -43,6 +43,7 @@ def parse():
     ap.add_argument("--no-mfma", action="store_true", help="skip the int8 matrix-core comparison timing")
     ap.add_argument("--no-requant", action="store_true", help="skip timing the fused re-quantising call")
     ap.add_argument("--no-two-stage", action="store_true", help="skip timing the literal two-stage form")
+    ap.add_argument("--no-quantizers", action="store_true", help="skip timing the quantiser / aggregation kernels")
     ap.add_argument("--only", default=None, metavar="LAYER,KW,KA",
                     help="restrict the workload to one case (layer index and bitwidths), e.g. 0,2,2")
     ap.add_argument("--traffic-pass", action="store_true",
@@ -391,6 +392,49 @@ def main():
             "fused_speedup": round((s1_us + s2_us) / conv_us_sum, 3),
         }
 
+    # ---- NEXT row: quantisers (Eq. 1a-1c) and aggregated quantisation functions (Eq. 6-7) on tensors of the
+    #      workload's largest layer: its input activations and the largest filter bank
+    quant = None
+    if not args.no_quantizers:
+        La = max((c.layer for c in cases), key=lambda L: L.N * L.H * L.W * L.C)
+        Lw = max((c.layer for c in cases), key=lambda L: L.K * L.R * L.S * L.C)
+        na, nw = La.N * La.H * La.W * La.C, Lw.K * Lw.R * Lw.S * Lw.C
+        gen = torch.Generator(device=dev).manual_seed(1234)
+        xa = (torch.randn(na, device=dev, generator=gen).abs_() * 3.0)
+        xw = torch.randn(nw, device=dev, generator=gen) * 0.3
+        lva = torch.empty(na, dtype=torch.uint8, device=dev)
+        lvw = torch.empty(nw, dtype=torch.uint8, device=dev)
+        oa = torch.empty(na, dtype=torch.float32, device=dev)
+        ow = torch.empty(nw, dtype=torch.float32, device=dev)
+        ws = torch.zeros(ebs.QUANT_WORKSPACE_BYTES // 4, dtype=torch.int32, device=dev)
+        cand = [1, 2, 3, 4, 5]
+        r = torch.zeros(5, dtype=torch.float32, device=dev)
+
+        def timed(f, reps=10):
+            f()
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+            ev[0].record(stream)
+            for _ in range(reps):
+                f()
+            ev[1].record(stream)
+            torch.cuda.synchronize()
+            return ev[0].elapsed_time(ev[1]) * 1e3 / reps
+
+        t_qa = timed(lambda: ebs.ebs_quantize_activations(xa, na, 6.0, 4, lva, stream))
+        t_aa = timed(lambda: ebs.ebs_aggregate_activations(xa, na, 6.0, cand, r, None, 1.0, oa, ws, stream))
+        t_qw = timed(lambda: ebs.ebs_quantize_weights(xw, nw, 4, lvw, ws, stream))
+        t_aw = timed(lambda: ebs.ebs_aggregate_weights(xw, nw, cand, r, None, 1.0, ow, ws, stream))
+        quant = {
+            "activation_elements": na, "weight_elements": nw,
+            "quantize_activations": {"us": round(t_qa, 2), "bound": "hbm", "achieved_gbs": round(5 * na / t_qa / 1e3, 1),
+                                     "frac": round(5 * na / t_qa / 1e3 / HBM_PEAK_GBS, 4)},
+            "aggregate_activations_5_candidates": {"us": round(t_aa, 2), "bound": "hbm", "achieved_gbs": round(8 * na / t_aa / 1e3, 1),
+                                                   "frac": round(8 * na / t_aa / 1e3 / HBM_PEAK_GBS, 4)},
+            "quantize_weights": {"us": round(t_qw, 2), "gelem_per_s": round(nw / t_qw / 1e3, 2),
+                                 "note": "double-precision tanh per element + max reduction; offline per step"},
+            "aggregate_weights_5_candidates": {"us": round(t_aw, 2), "gelem_per_s": round(nw / t_aw / 1e3, 2)},
+        }
+
     traffic = read_traffic(args.workload)
     if traffic is not None:
         roofline["traffic"] = traffic
@@ -412,6 +456,8 @@ def main():
         out["requant_epilogue"] = requant
     if two_stage is not None:
         out["two_stage_comparison"] = two_stage
+    if quant is not None:
+        out["quantizers"] = quant
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cases)
     cases_out = args.cases_out

@@ -14,6 +14,12 @@ from .binding import (  # noqa: F401
     ebs_mixed_conv2d_requant,
     ebs_mixed_conv2d_signed,
     ebs_partial_products_bytes,
+    ebs_quantize_weights,
+    ebs_quantize_activations,
+    ebs_aggregate_weights,
+    ebs_aggregate_activations,
+    QUANT_WORKSPACE_BYTES,
+    MAX_CANDIDATES,
     ebs_binary_conv_planes,
     ebs_pow2_depthwise,
     ebs_mixed_conv2d_variant,

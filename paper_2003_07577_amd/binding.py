@@ -73,6 +73,15 @@ def load_library():
         lib.ebs_binary_conv_planes.argtypes = [_vp, _vp] + [_ci] * 11 + [_vp, _vp]
         lib.ebs_pow2_depthwise.restype = _ci
         lib.ebs_pow2_depthwise.argtypes = [_vp, ctypes.c_longlong, _ci, _ci, _ci, _vp, _vp, _ci, _vp, _vp, _vp]
+        _sz, _fl = ctypes.c_size_t, ctypes.c_float
+        lib.ebs_quantize_weights.restype = _ci
+        lib.ebs_quantize_weights.argtypes = [_vp, _sz, _ci, _vp, _vp, _vp]
+        lib.ebs_quantize_activations.restype = _ci
+        lib.ebs_quantize_activations.argtypes = [_vp, _sz, _fl, _ci, _vp, _vp]
+        lib.ebs_aggregate_weights.restype = _ci
+        lib.ebs_aggregate_weights.argtypes = [_vp, _sz, ctypes.POINTER(_ci), _ci, _vp, _vp, _fl, _vp, _vp, _vp]
+        lib.ebs_aggregate_activations.restype = _ci
+        lib.ebs_aggregate_activations.argtypes = [_vp, _sz, _fl, ctypes.POINTER(_ci), _ci, _vp, _vp, _fl, _vp, _vp, _vp]
         lib.ebs_conv_variant_count.restype = _ci
         lib.ebs_conv_variant_name.restype = ctypes.c_char_p
         lib.ebs_conv_variant_name.argtypes = [_ci]
@@ -191,6 +200,48 @@ def ebs_pow2_depthwise(planes, positions, K, k_w, k_a, scale, offset, per_channe
         _ptr(acc_out), _ptr(out_f32), _stream(stream))
     if check:
         _check(rc, "ebs_pow2_depthwise")
+    return rc
+
+
+QUANT_WORKSPACE_BYTES = 256     # EBS_QUANT_WORKSPACE_BYTES
+MAX_CANDIDATES = 8              # EBS_MAX_CANDIDATES
+
+
+def _int_array(values):
+    values = [int(v) for v in values]
+    return (ctypes.c_int * max(len(values), 1))(*values), len(values)
+
+
+def ebs_quantize_weights(w, count, k_w, levels, workspace, stream=None, check=True) -> int:
+    rc = load_library().ebs_quantize_weights(_ptr(w), count, k_w, _ptr(levels), _ptr(workspace), _stream(stream))
+    if check:
+        _check(rc, "ebs_quantize_weights")
+    return rc
+
+
+def ebs_quantize_activations(x, count, alpha, k_a, levels, stream=None, check=True) -> int:
+    rc = load_library().ebs_quantize_activations(_ptr(x), count, alpha, k_a, _ptr(levels), _stream(stream))
+    if check:
+        _check(rc, "ebs_quantize_activations")
+    return rc
+
+
+def ebs_aggregate_weights(w, count, bits, strengths, gumbel, tau, w_hat, workspace, stream=None, check=True) -> int:
+    arr, n = _int_array(bits)
+    rc = load_library().ebs_aggregate_weights(_ptr(w), count, arr, n, _ptr(strengths), _ptr(gumbel), tau,
+                                              _ptr(w_hat), _ptr(workspace), _stream(stream))
+    if check:
+        _check(rc, "ebs_aggregate_weights")
+    return rc
+
+
+def ebs_aggregate_activations(x, count, alpha, bits, strengths, gumbel, tau, x_hat, workspace, stream=None,
+                              check=True) -> int:
+    arr, n = _int_array(bits)
+    rc = load_library().ebs_aggregate_activations(_ptr(x), count, alpha, arr, n, _ptr(strengths), _ptr(gumbel), tau,
+                                                  _ptr(x_hat), _ptr(workspace), _stream(stream))
+    if check:
+        _check(rc, "ebs_aggregate_activations")
     return rc
 
 

@@ -270,6 +270,69 @@ int ebs_mixed_conv2d_requant(const void *packed_act, const void *packed_wgt,
     return rc;
 }
 
+static bool finite_pos(float v) { return v > 0.0f && v < 3.0e38f; }
+static int check_elementwise(const void *in, const void *out, size_t count)
+{
+    if (!in || !out) return EBS_ERR_NULL;
+    if (count == 0 || count >= ((size_t)1 << 40)) return EBS_ERR_SHAPE;
+    if (!aligned16(in) || !aligned16(out)) return EBS_ERR_ALIGN;
+    return EBS_OK;
+}
+static int check_candidates(const int *bits, int n_bits, const float *strengths, const float *gumbel, float tau)
+{
+    if (!bits || !strengths) return EBS_ERR_NULL;
+    if (n_bits < 1 || n_bits > kMaxCandidates) return EBS_ERR_BITWIDTH;
+    for (int i = 0; i < n_bits; ++i)
+        if (bits[i] < 1 || bits[i] > 8) return EBS_ERR_BITWIDTH;
+    if (gumbel && !finite_pos(tau)) return EBS_ERR_SHAPE;
+    return EBS_OK;
+}
+
+int ebs_quantize_weights(const float *w, size_t count, int k_w, uint8_t *levels, void *workspace, void *stream)
+{
+    if (!workspace) return EBS_ERR_NULL;
+    int rc = check_elementwise(w, levels, count);
+    if (rc) return rc;
+    if (k_w < 1 || k_w > 8) return EBS_ERR_BITWIDTH;
+    if (!aligned16(workspace)) return EBS_ERR_ALIGN;
+    return quantize_weights(w, count, k_w, levels, workspace, (hipStream_t)stream);
+}
+
+int ebs_quantize_activations(const float *x, size_t count, float alpha, int k_a, uint8_t *levels, void *stream)
+{
+    int rc = check_elementwise(x, levels, count);
+    if (rc) return rc;
+    if (k_a < 1 || k_a > 8) return EBS_ERR_BITWIDTH;
+    if (!finite_pos(alpha)) return EBS_ERR_SHAPE;
+    return quantize_activations(x, count, alpha, k_a, levels, (hipStream_t)stream);
+}
+
+int ebs_aggregate_weights(const float *w, size_t count, const int *bits, int n_bits, const float *strengths,
+                          const float *gumbel, float tau, float *w_hat, void *workspace, void *stream)
+{
+    if (!workspace) return EBS_ERR_NULL;
+    int rc = check_elementwise(w, w_hat, count);
+    if (rc) return rc;
+    rc = check_candidates(bits, n_bits, strengths, gumbel, tau);
+    if (rc) return rc;
+    if (!aligned16(workspace)) return EBS_ERR_ALIGN;
+    return aggregate_weights(w, count, bits, n_bits, strengths, gumbel, tau, w_hat, workspace, (hipStream_t)stream);
+}
+
+int ebs_aggregate_activations(const float *x, size_t count, float alpha, const int *bits, int n_bits,
+                              const float *strengths, const float *gumbel, float tau, float *x_hat,
+                              void *workspace, void *stream)
+{
+    if (!workspace) return EBS_ERR_NULL;
+    int rc = check_elementwise(x, x_hat, count);
+    if (rc) return rc;
+    rc = check_candidates(bits, n_bits, strengths, gumbel, tau);
+    if (rc) return rc;
+    if (!finite_pos(alpha)) return EBS_ERR_SHAPE;
+    if (!aligned16(workspace)) return EBS_ERR_ALIGN;
+    return aggregate_activations(x, count, alpha, bits, n_bits, strengths, gumbel, tau, x_hat, workspace, (hipStream_t)stream);
+}
+
 int ebs_check_levels(const uint8_t *levels, size_t count, int bits, int32_t *device_flag, void *stream)
 {
     if (!levels || !device_flag) return EBS_ERR_NULL;

@@ -14,6 +14,8 @@ constexpr int kWgtGroup = 16;
 // Largest bitwidth of weights and activations: the search space of the paper is {1, ..., 5}
 // (Sec. 5, implementation details).
 constexpr int kMaxBits = 5;
+// Candidate bitwidths of one aggregated quantisation function (Sec. 3.1); the paper searches five.
+constexpr int kMaxCandidates = EBS_MAX_CANDIDATES;
 
 struct ConvArgs {
     const uint32_t *act;   // packed activations  [N][H+2][W+2][cw][k_a], zero border of one position
@@ -57,6 +59,13 @@ int launch_planes_tiled(const ConvArgs &a);      // EBS_ERR_UNSUPPORTED when the
 int launch_planes_naive(const ConvArgs &a);
 int launch_pow2_depthwise(const int32_t *planes, long long plane_elems, int K, int kw, int ka, const float *scale,
                           const float *offset, int per_channel, int32_t *acc, float *out, hipStream_t st);
+// Quantisers and aggregated quantisation functions (quantize.hip); workspace: 256 device bytes.
+int quantize_weights(const float *w, size_t count, int bits, uint8_t *levels, void *workspace, hipStream_t st);
+int quantize_activations(const float *x, size_t count, float alpha, int bits, uint8_t *levels, hipStream_t st);
+int aggregate_weights(const float *w, size_t count, const int *bits, int n, const float *strengths, const float *gumbel,
+                      float tau, float *out, void *workspace, hipStream_t st);
+int aggregate_activations(const float *x, size_t count, float alpha, const int *bits, int n, const float *strengths,
+                          const float *gumbel, float tau, float *out, void *workspace, hipStream_t st);
 int conv_tiled_variant_count();
 const char *conv_tiled_variant_name(int variant);
 

@@ -41,6 +41,23 @@ def test_version_and_status_strings(lib):
     assert ebs.ebs_last_hip_error() == "hipSuccess"      # no launch has failed in this thread
 
 
+def test_quantizer_calls_reject_bad_arguments_on_the_host(lib):
+    ok = dict(w=FAKE, count=64, k=2, levels=FAKE, ws=FAKE)
+    q = lambda **kw: (lambda d: ebs.ebs_quantize_weights(d["w"], d["count"], d["k"], d["levels"], d["ws"], check=False))({**ok, **kw})
+    assert q(w=None) == -1 and q(levels=None) == -1 and q(ws=None) == -1
+    assert q(k=0) == -2 and q(k=9) == -2
+    assert q(count=0) == -3
+    assert q(w=FAKE + 4) == -4 and q(ws=FAKE + 8) == -4
+    a = lambda alpha, k: ebs.ebs_quantize_activations(FAKE, 64, alpha, k, FAKE, check=False)
+    assert a(0.0, 2) == -3 and a(float("inf"), 2) == -3 and a(float("nan"), 2) == -3 and a(6.0, 0) == -2
+    agg = lambda bits, tau=1.0, g=None, r=FAKE: ebs.ebs_aggregate_weights(FAKE, 64, bits, r, g, tau, FAKE, FAKE, check=False)
+    assert agg([]) == -2 and agg([1] * (ebs.MAX_CANDIDATES + 1)) == -2 and agg([0, 2]) == -2 and agg([2, 9]) == -2
+    assert agg([2, 3], r=None) == -1
+    assert agg([2, 3], tau=0.0, g=FAKE) == -3 and agg([2, 3], tau=-1.0, g=FAKE) == -3
+    act = lambda alpha: ebs.ebs_aggregate_activations(FAKE, 64, alpha, [2, 3], FAKE, None, 1.0, FAKE, FAKE, check=False)
+    assert act(0.0) == -3 and act(float("nan")) == -3
+
+
 def test_packed_sizes(lib):
     # activations: N*(H+2)*(W+2) positions x ceil(C/32) words x k_a planes x 4 bytes + 16 slack bytes
     assert ebs.ebs_packed_activations_bytes(64, 56, 56, 64, 4) == 64 * 58 * 58 * 2 * 4 * 4 + 16
