@@ -345,7 +345,7 @@ def main():
             t_us += us
             del nxt
         requant = {
-            "kernel": "ebs_mixed_conv2d_requant (conv + next layer's quantiser + bit-plane packing, incl. zero-ring kernel)",
+            "kernel": "ebs_mixed_conv2d_requant (conv + next layer's quantiser + bit-plane packing + zero ring, one kernel)",
             "binary_tops": round(conv_ops / t_us / 1e6, 1), "frac_of_alu_roof": round(conv_ops / t_us / 1e6 / PEAK_BINARY_TOPS, 4),
             "vs_pack_plus_conv": round((conv_us_sum + pack_us_sum) / t_us, 3),
         }

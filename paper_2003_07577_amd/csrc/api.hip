@@ -263,11 +263,11 @@ int ebs_mixed_conv2d_requant(const void *packed_act, const void *packed_wgt,
     rc = check_act_shape(N, a.OH, a.OW, K);          // the next layer's packed tensor must be addressable
     if (rc) return rc;
     a.wtop = signed_weights ? (1 << k_w) - 1 : 0;
+    rc = launch_requant_tiled(a);                     // writes the zero ring itself
+    if (rc != EBS_ERR_UNSUPPORTED) return rc;
     rc = launch_zero_border(a.next, N, a.OH, a.OW, words_per_pixel(K) * k_next, a.stream);
     if (rc) return rc;
-    rc = launch_requant_tiled(a);
-    if (rc == EBS_ERR_UNSUPPORTED) rc = launch_requant_naive(a);
-    return rc;
+    return launch_requant_naive(a);
 }
 
 static bool finite_pos(float v) { return v > 0.0f && v < 3.0e38f; }

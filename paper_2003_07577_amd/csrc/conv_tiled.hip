@@ -101,11 +101,18 @@ static int kt_of(int budget, int kw, int ka)
     return t[kw + ka - 2];
 }
 
-// Fused re-quantisation: the K4 kernels whose work-groups own whole 32-channel words.
+// Fused re-quantisation: the K4 kernels whose work-groups own whole 32-channel words; layers with few
+// positions and a long reduction split the reduction among the waves instead (work-groups of 8 channels).
 int launch_requant_tiled(const ConvArgs &a)
 {
-    const int order[2] = {ch_slot(a.cw), 1};       // preferred chunk size, then the smallest footprint
-    for (int i = 0; i < 2; ++i) {
+    const long long positions = (long long)a.N * a.OH * a.OW;
+    const int rs = a.R * a.S;
+    int order[3];
+    int n = 0;
+    if (rs > 1 && rs * a.cw >= 64 && positions <= 16384 && a.cw % 4 == 0) order[n++] = 3;
+    order[n++] = ch_slot(a.cw);       // preferred chunk size
+    order[n++] = 1;                   // single-word chunks: the smallest footprint
+    for (int i = 0; i < n; ++i) {
         int rc = (a.R == 3 && a.S == 3) ? run_req_fs<3>(a, order[i]) : run_req_fs<0>(a, order[i]);
         if (rc != EBS_ERR_UNSUPPORTED) return rc;
     }

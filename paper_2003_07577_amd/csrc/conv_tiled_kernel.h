@@ -74,6 +74,7 @@ struct TiledShape {
     // fused re-quantisation (REQ kernels only): next layer's quantiser and packed layout
     float alpha, qs;
     int k_next, OHn, OWn, cwn;     // bordered output grid (OH+2, OW+2), words per position of the next layer
+    int ring_total, ring_per_image;  // dwords of the zero ring of the next layer's packed tensor (all images / one)
     int wtop;         // 0: unsigned weight levels; else 2^k_w - 1 (signed weights 2q - wtop, Eq. 1a)
     int dbg;          // experiment switches; only read in EBS_EXPERIMENT builds
 };
@@ -123,6 +124,10 @@ struct Cfg {
     static constexpr int OCOLS = KB;
     static constexpr int OPITCH = OCOLS + 4;
     static constexpr int OUT_DWORDS = OROWS * OPITCH;
+    // fused re-quantisation: bit pieces of the next layer's words, bytes [position][plane][8-channel group]
+    static constexpr int REQ_NG = KB / 8;                  // 8-channel groups of a work-group (4 per packed word)
+    static constexpr int REQ_ROWB = kMaxBits * REQ_NG;     // bytes per position
+    static constexpr int REQ_DWORDS = (TP * REQ_ROWB + 3) / 4;
     static_assert(CH % WRED == 0, "chunk must divide among the waves");
     static_assert(KT % 4 == 0 && (KT <= 16 ? 16 % KT == 0 : KT % 16 == 0), "channel tile vs weight group");
     static_assert(256 % (OCOLS / 4) == 0, "write-back assumes a fixed column group per thread");
@@ -413,6 +418,136 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
         }
     }
 
+    if constexpr (REQ) {
+        // ---- fused re-quantisation (Eq. 1b-1c) and bit-plane packing of the next layer's activations.
+        //      A lane holds KT channels of its positions: it quantises them and builds for every plane the
+        //      KT-bit piece "bit j of the levels".  K4: the pieces go to LDS, bytes [position][plane][group of
+        //      8 channels]; the four pieces of a 32-channel word are then one aligned dword, which the
+        //      write-out copies to the packed tensor.  R4: the partial sums of the four waves first meet in
+        //      LDS; the work-group owns 8 channels, one byte of each word, which wave 0 stores directly.
+        //      Every work-group also clears its share of the zero ring.
+        static_assert(!REQ || (MODE == MODE_K4 && KT % 8 == 0 && C::KB % 32 == 0) || (MODE == MODE_R4 && KT == 8 && PIX == 1),
+                      "re-quantising kernels own whole bytes of the packed words");
+        const int kmax = sh.k_next;
+        int32_t sums[PIX][KT];
+#pragma unroll
+        for (int p = 0; p < PIX; ++p) {
+            uint32_t ws = 0;
+            if constexpr (SGN) {
+#pragma unroll
+                for (int j = 0; j < KA; ++j) ws += wsum_cls[p][j] << j;
+            }
+#pragma unroll
+            for (int c = 0; c < KT; ++c) {
+                uint32_t v = 0;
+#pragma unroll
+                for (int sft = 0; sft < C::NCLS; ++sft) v += cls[p][c][sft] << sft;       // Eq. 14
+                sums[p][c] = (int32_t)v;
+                if constexpr (SGN) sums[p][c] = 2 * sums[p][c] - sh.wtop * (int32_t)ws;   // linear: also for partial sums
+            }
+        }
+        if constexpr (MODE == MODE_R4) {
+            if (wave == 0) {
+#pragma unroll
+                for (int c = 0; c < KT; c += 4) {
+                    i32x4 v = {sums[0][c], sums[0][c + 1], sums[0][c + 2], sums[0][c + 3]};
+                    *reinterpret_cast<i32x4 *>(otile + lane * C::OPITCH + c) = v;
+                }
+            }
+            __syncthreads();
+            if (wave != 0) {
+#pragma unroll
+                for (int c = 0; c < KT; ++c) atomicAdd(&otile[lane * C::OPITCH + c], sums[0][c]);
+            }
+            __syncthreads();
+            if (wave == 0) {
+#pragma unroll
+                for (int c = 0; c < KT; c += 4) {
+                    const i32x4 v = *reinterpret_cast<const i32x4 *>(otile + lane * C::OPITCH + c);
+                    sums[0][c] = v[0]; sums[0][c + 1] = v[1]; sums[0][c + 2] = v[2]; sums[0][c + 3] = v[3];
+                }
+            }
+        }
+        uint8_t *pieces = reinterpret_cast<uint8_t *>(otile);
+        if (MODE != MODE_R4 || wave == 0) {
+#pragma unroll
+            for (int p = 0; p < PIX; ++p) {
+                uint32_t piece[kMaxBits];
+#pragma unroll
+                for (int j = 0; j < kMaxBits; ++j) piece[j] = 0u;
+#pragma unroll
+                for (int c = 0; c < KT; ++c) {
+                    const int k = k0 + c;                      // wave-uniform: scalar loads
+                    const int kc = k < sh.K ? k : sh.K - 1;
+                    const int ci = sh.per_channel ? kc : 0;
+                    const uint32_t lv = k < sh.K ? requant_level(sums[p][c], scale[ci], offset ? offset[ci] : 0.0f, sh.alpha, sh.qs) : 0u;
+#pragma unroll
+                    for (int j = 0; j < kMaxBits; ++j) piece[j] |= ((lv >> j) & 1u) << c;
+                }
+                const int row = p * 64 + lane;
+                if constexpr (MODE == MODE_R4) {
+                    const int t = t_first + row;
+                    if (t < sh.total && !EBS_DBG(1)) {
+                        const int n = (int)fd_div((uint32_t)t, sh.div_ohow);
+                        const int rem = t - n * (int)sh.div_ohow.d;
+                        const int oh = (int)fd_div((uint32_t)rem, sh.div_ow);
+                        const int ow = rem - oh * sh.OW;
+                        const size_t pos = ((size_t)n * sh.OHn + oh + kActBorder) * sh.OWn + ow + kActBorder;
+                        uint8_t *dstb = reinterpret_cast<uint8_t *>(packed_next + (pos * sh.cwn + (kb0 >> 5)) * kmax) + ((kb0 >> 3) & 3);
+#pragma unroll
+                        for (int j = 0; j < kMaxBits; ++j)
+                            if (j < kmax) dstb[4 * j] = (uint8_t)piece[j];
+                    }
+                } else {
+                    uint8_t *dst = pieces + row * C::REQ_ROWB + wk * (KT / 8);
+#pragma unroll
+                    for (int j = 0; j < kMaxBits; ++j) {
+                        if (j < kmax) {
+                            if constexpr (KT == 8) dst[j * C::REQ_NG] = (uint8_t)piece[j];
+                            else *reinterpret_cast<uint16_t *>(dst + j * C::REQ_NG) = (uint16_t)piece[j];
+                        }
+                    }
+                }
+            }
+        }
+        if (EBS_DBG(1)) return;
+        if constexpr (MODE != MODE_R4) {
+            __syncthreads();
+            constexpr int WPB = C::KB / 32;                // packed words of a position this work-group owns
+            const int word0 = kb0 >> 5;
+            const int items = C::TP * WPB;
+            for (int it = tid; it < items; it += 256) {
+                const int row = it / WPB;
+                const int wd = it - row * WPB;
+                const int t = t_first + row;
+                if (t >= sh.total || word0 + wd >= sh.cwn) continue;
+                const int n = (int)fd_div((uint32_t)t, sh.div_ohow);
+                const int rem = t - n * (int)sh.div_ohow.d;
+                const int oh = (int)fd_div((uint32_t)rem, sh.div_ow);
+                const int ow = rem - oh * sh.OW;
+                const size_t pos = ((size_t)n * sh.OHn + oh + kActBorder) * sh.OWn + ow + kActBorder;
+                uint32_t *dstw = packed_next + (pos * sh.cwn + word0 + wd) * kmax;
+                const uint8_t *src = pieces + row * C::REQ_ROWB + wd * 4;
+                for (int j = 0; j < kmax; ++j) dstw[j] = *reinterpret_cast<const uint32_t *>(src + j * C::REQ_NG);
+            }
+        }
+        // zero ring of the next layer's tensor, dealt evenly to the work-groups: top row, bottom row,
+        // then the left/right columns of every image
+        const int wpp = sh.cwn * kmax;
+        for (int idx = logical * 256 + tid; idx < sh.ring_total; idx += sh.nblocks * 256) {
+            const int n = idx / sh.ring_per_image;
+            const int rem = idx - n * sh.ring_per_image;
+            const int b = rem / wpp;
+            const int word = rem - b * wpp;
+            int hp, wp;
+            if (b < sh.OWn) { hp = 0; wp = b; }
+            else if (b < 2 * sh.OWn) { hp = sh.OHn - 1; wp = b - sh.OWn; }
+            else { const int cc = b - 2 * sh.OWn; hp = 1 + (cc >> 1); wp = (cc & 1) ? sh.OWn - 1 : 0; }
+            packed_next[(((size_t)n * sh.OHn + hp) * sh.OWn + wp) * wpp + word] = 0u;
+        }
+        return;
+    }
+
     // ---- epilogue through LDS: [position][channel] tile, then coalesced write-back
     constexpr int CG = C::OCOLS / 4;              // 16-byte column groups per row
     constexpr int RSTEP = 256 / CG;               // rows covered by one sweep of the work-group
@@ -490,39 +625,7 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
             __syncthreads();
             if (EBS_DBG(1)) continue;
             // rows of this pass: row r of sub-tile w is position t_first + w*TPW + p*64 + r
-            if constexpr (REQ) {
-                // ---- fused re-quantisation (Eq. 1b-1c) and bit-plane packing for the next layer: the 8
-                //      threads that hold the 32 channels of one word OR their 4-bit pieces together
-                static_assert(!REQ || (CG % 8 == 0), "a packed word needs all 32 channels in one work-group");
-#pragma unroll
-                for (int r0 = 0; r0 < C::OROWS; r0 += RSTEP) {
-                    const int row = r0 + tid / CG;
-                    const int t = t_first + (row >> 6) * C::TPW + p * 64 + (row & 63);
-                    const bool valid = row < C::OROWS && t < sh.total;
-                    const int rr = row < C::OROWS ? row : 0;
-                    const i32x4 v = *reinterpret_cast<const i32x4 *>(otile + rr * C::OPITCH + cg * 4);
-                    uint32_t lv[4];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        lv[e] = kq + e < sh.K ? requant_level(v[e], sc[e], of[e], sh.alpha, sh.qs) : 0u;
-                    const int tc = valid ? t : t_first;
-                    const int n = (int)fd_div((uint32_t)tc, sh.div_ohow);
-                    const int rem = tc - n * (int)sh.div_ohow.d;
-                    const int oh = (int)fd_div((uint32_t)rem, sh.div_ow);
-                    const int ow = rem - oh * sh.OW;
-                    const size_t pos = ((size_t)n * sh.OHn + oh + kActBorder) * sh.OWn + ow + kActBorder;
-                    const int word = kq >> 5;
-                    uint32_t *dst = packed_next + (pos * sh.cwn + word) * sh.k_next;
-                    for (int j = 0; j < sh.k_next; ++j) {
-                        uint32_t w = (((lv[0] >> j) & 1u) | (((lv[1] >> j) & 1u) << 1) | (((lv[2] >> j) & 1u) << 2) |
-                                      (((lv[3] >> j) & 1u) << 3)) << (4 * (cg & 7));
-                        w |= (uint32_t)__shfl_xor((int)w, 1);
-                        w |= (uint32_t)__shfl_xor((int)w, 2);
-                        w |= (uint32_t)__shfl_xor((int)w, 4);
-                        if (valid && (cg & 7) == 0 && word < sh.cwn) dst[j] = w;
-                    }
-                }
-            } else {
+            {
 #pragma unroll
             for (int r0 = 0; r0 < C::OROWS; r0 += RSTEP) {
                 const int row = r0 + tid / CG;
@@ -575,6 +678,10 @@ EBS_TILE(16, 5, 1, 4)   EBS_TILE(16, 6, 1, 4)   EBS_TILE(16, 7, 1, 4)   EBS_TILE
 // work-group hold whole 32-channel words of the next layer's packed activations)
 EBS_TILE(8, 1, 1, 16)   EBS_TILE(8, 2, 1, 8)    EBS_TILE(8, 3, 1, 8)   EBS_TILE(8, 4, 1, 8)
 EBS_TILE(8, 5, 1, 8)    EBS_TILE(8, 6, 1, 8)    EBS_TILE(8, 7, 1, 8)    EBS_TILE(8, 8, 1, 8)   EBS_TILE(8, 9, 1, 8)
+// budget 7: re-quantising kernels that split the reduction among the waves (MODE_R4): a work-group
+// owns 8 channels, one byte of each packed word of the next layer
+EBS_TILE(7, 1, 1, 8)    EBS_TILE(7, 2, 1, 8)    EBS_TILE(7, 3, 1, 8)   EBS_TILE(7, 4, 1, 8)
+EBS_TILE(7, 5, 1, 8)    EBS_TILE(7, 6, 1, 8)    EBS_TILE(7, 7, 1, 8)    EBS_TILE(7, 8, 1, 8)   EBS_TILE(7, 9, 1, 8)
 #undef EBS_TILE
 
 // Tile of a (budget, k_w, k_a) kernel.  Budget 4 is the plane-pair kernel (MODE_PL): one
@@ -636,13 +743,18 @@ static int launch_cfg(const ConvArgs &a)
         sh.OHn = a.OH + 2 * kActBorder;
         sh.OWn = a.OW + 2 * kActBorder;
         sh.cwn = words_per_pixel(a.K);
+        const long long ring_pos = 2LL * sh.OWn + 2LL * a.OH;          // ring positions of one image
+        const long long per_image = ring_pos * sh.cwn * a.k_next;
+        if (per_image * a.N > (1LL << 30)) return EBS_ERR_UNSUPPORTED;
+        sh.ring_per_image = (int)per_image;
+        sh.ring_total = (int)(per_image * a.N);
     }
 
     TileGeom g{a.H, a.W, a.R, a.S, a.stride, a.pad, a.OH, a.OW, kActBorder};
     long long tp = C::TP < sh.total ? C::TP : sh.total;
     long long ucap = g.extent_bound(tp);
     long long stage_dwords = (ucap * C::POSW + 3) / 4 * 4;
-    size_t lds_bytes = (size_t)(stage_dwords + C::OUT_DWORDS) * sizeof(uint32_t);
+    size_t lds_bytes = (size_t)(stage_dwords + ((REQ && MODE != MODE_R4) ? C::REQ_DWORDS : C::OUT_DWORDS)) * sizeof(uint32_t);
     if (lds_bytes > kMaxLdsBytes || ucap > (1 << 28)) return EBS_ERR_UNSUPPORTED;
     sh.ucap = (int)ucap;
     sh.stage_dwords = (int)stage_dwords;
@@ -652,6 +764,7 @@ static int launch_cfg(const ConvArgs &a)
 
     long long ptiles = ((long long)sh.total + C::TP - 1) / C::TP;
     long long kblocks = ((long long)a.K + C::KB - 1) / C::KB;
+    if (REQ && MODE == MODE_R4) kblocks = 4LL * words_per_pixel(a.K);   // every byte of every packed word has an owner
     long long nblocks = ptiles * kblocks;
     if (nblocks > (1LL << 30)) return EBS_ERR_UNSUPPORTED;
     sh.kblocks = (int)kblocks;
@@ -719,24 +832,24 @@ static int launch_bits(const ConvArgs &a, int v)
     }
 }
 
-// Re-quantising kernels: K4 arrangement, chunk sizes 2 / 1 / 4 (variant 0 / 1 / 2).
+// Re-quantising kernels: K4 arrangement with chunk sizes 2 / 1 / 4 (variants 0 / 1 / 2), and the
+// reduction-split arrangement for layers with few positions and a long reduction (variant 3).
+template <int KW, int KA, int FS, bool SGN>
+static int launch_bits_req_sgn(const ConvArgs &a, int v)
+{
+    switch (v) {
+        case 0: return launch_cfg<KW, KA, 8, 2, MODE_K4, FS, true, SGN>(a);
+        case 1: return launch_cfg<KW, KA, 8, 1, MODE_K4, FS, true, SGN>(a);
+        case 2: return launch_cfg<KW, KA, 8, 4, MODE_K4, FS, true, SGN>(a);
+        case 3: return launch_cfg<KW, KA, 7, 4, MODE_R4, FS, true, SGN>(a);
+    }
+    return EBS_ERR_UNSUPPORTED;
+}
+
 template <int KW, int KA, int FS>
 static int launch_bits_req(const ConvArgs &a, int v)
 {
-    if (a.wtop) {
-        switch (v) {
-            case 0: return launch_cfg<KW, KA, 8, 2, MODE_K4, FS, true, true>(a);
-            case 1: return launch_cfg<KW, KA, 8, 1, MODE_K4, FS, true, true>(a);
-            case 2: return launch_cfg<KW, KA, 8, 4, MODE_K4, FS, true, true>(a);
-        }
-        return EBS_ERR_UNSUPPORTED;
-    }
-    switch (v) {
-        case 0: return launch_cfg<KW, KA, 8, 2, MODE_K4, FS, true>(a);
-        case 1: return launch_cfg<KW, KA, 8, 1, MODE_K4, FS, true>(a);
-        case 2: return launch_cfg<KW, KA, 8, 4, MODE_K4, FS, true>(a);
-    }
-    return EBS_ERR_UNSUPPORTED;
+    return a.wtop ? launch_bits_req_sgn<KW, KA, FS, true>(a, v) : launch_bits_req_sgn<KW, KA, FS, false>(a, v);
 }
 
 // Plane-pair kernels (stage 1 of the two-stage form): chunk sizes 1 / 4 (variant 0 / 1); the

@@ -45,7 +45,9 @@ GEOS = [  # N, C, H, W, K, R, S, stride, pad
     (1, 32, 13, 7, 17, 1, 1, 1, 0),       # 1x1, K < 32
     (2, 128, 8, 8, 130, 3, 3, 1, 1),      # K = 4 words + 2 channels
     (2, 33, 8, 8, 70, 5, 5, 1, 2),        # pad 2: fallback kernel
-    (1, 256, 7, 7, 96, 3, 3, 1, 1),
+    (1, 256, 7, 7, 96, 3, 3, 1, 1),       # few positions, long reduction: reduction-split kernel
+    (2, 256, 6, 6, 50, 3, 3, 1, 1),       # the same with K ragged against the bytes and words of the packed output
+    (1, 128, 9, 9, 7, 3, 3, 2, 1),        # reduction-split, K < 8
 ]
 
 
