@@ -174,7 +174,7 @@ static int reduce_absmax(const float *w, size_t count, uint32_t *ws, hipStream_t
 {
     hipLaunchKernelGGL(quant_ws_clear, dim3(1), dim3(1), 0, st, ws);
     size_t want = (count + 255) / 256;
-    unsigned blocks = (unsigned)(want < 2048 ? want : 2048);
+    unsigned blocks = (unsigned)(want < 256 ? want : 256);       // one atomic per block on a single address: keep them few
     hipLaunchKernelGGL(absmax_kernel, dim3(blocks), dim3(256), 0, st, w, count, ws);
     return hip_ok(hipGetLastError());
 }
