@@ -38,7 +38,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="resnet18", choices=sorted(WORKLOADS))
-    ap.add_argument("--kernel-reps", type=int, default=10, help="back-to-back launches per case for per-kernel timing")
+    ap.add_argument("--kernel-reps", type=int, default=50, help="back-to-back launches per case for per-kernel timing (after 10 warm-up launches)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-mfma", action="store_true", help="skip the int8 matrix-core comparison timing")
     ap.add_argument("--no-requant", action="store_true", help="skip timing the fused re-quantising call")
@@ -113,6 +113,20 @@ def pack_bytes(case):
     L = case.layer
     cw = (L.C + 31) // 32
     return L.N * L.H * L.W * L.C + L.N * (L.H + 2) * (L.W + 2) * cw * case.k_a * 4
+
+
+def gpu_clocks():
+    """Shader and memory clock states as the driver reports them (the starred entry is the current one)."""
+    import glob
+    out = {}
+    for name in ("pp_dpm_sclk", "pp_dpm_mclk"):
+        for path in sorted(glob.glob(f"/sys/class/drm/card*/device/{name}")):
+            try:
+                out[name] = " ".join(open(path).read().split())
+                break
+            except OSError:
+                continue
+    return out or None
 
 
 def read_traffic(workload):
@@ -241,8 +255,9 @@ def main():
     for b in bufs:
         c = b.case
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
-        b.pack(ebs, stream)
-        b.conv(ebs, stream, args.variant)
+        for _ in range(10):
+            b.pack(ebs, stream)
+            b.conv(ebs, stream, args.variant)
         ev[0].record(stream)
         for _ in range(args.kernel_reps):
             b.pack(ebs, stream)
@@ -458,6 +473,9 @@ def main():
         out["two_stage_comparison"] = two_stage
     if quant is not None:
         out["quantizers"] = quant
+    clocks = gpu_clocks()
+    if clocks:
+        out["clocks"] = clocks
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cases)
     cases_out = args.cases_out
