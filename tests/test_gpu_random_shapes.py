@@ -1,0 +1,88 @@
+"""GPU parity on seeded random valid shapes: the fused, signed, re-quantising and two-stage calls against
+the oracle on geometries nobody hand-picked (ragged channels, 1-wide images, filters as large as the padded
+image, strides up to 3, every bit pair of {1..5}^2 drawn at random)."""
+import numpy as np
+import pytest
+
+import ebs_workloads as wl
+import paper_2003_07577_amd as ebs
+from gpu_harness import POISON, assert_f32_close, pack, unpack_activations, upload
+
+pytestmark = pytest.mark.gpu
+
+
+def _draw_geometry(rng):
+    while True:
+        R, S = (int(v) for v in rng.choice([1, 1, 2, 3, 3, 3, 5], 2))
+        if rng.random() < 0.6:
+            S = R
+        pad = int(rng.integers(0, min(R, S)))
+        stride = int(rng.choice([1, 1, 1, 2, 2, 3]))
+        H, W = int(rng.integers(1, 25)), int(rng.integers(1, 25))
+        if H + 2 * pad < R or W + 2 * pad < S:
+            continue
+        N = int(rng.integers(1, 4))
+        C = int(rng.choice([1, 3, 16, 31, 32, 33, 64, 96, 100, 128, 160, 256]))
+        K = int(rng.choice([1, 2, 7, 8, 15, 16, 17, 31, 32, 33, 40, 64, 65, 100, 128]))
+        if N * H * W * C > 400000 or K * R * S * C > 400000:
+            continue
+        return N, C, H, W, K, R, S, stride, pad
+
+
+@pytest.mark.parametrize("block", range(6))
+def test_random_shapes_all_entry_points(oracle_mod, block):
+    import torch
+    rng = np.random.default_rng(4242 + block)
+    for i in range(12):
+        N, C, H, W, K, R, S, st, pad = _draw_geometry(rng)
+        kw, ka = int(rng.integers(1, 6)), int(rng.integers(1, 6))
+        per_channel = bool(rng.integers(0, 2))
+        inp = wl.random_case(int(rng.integers(1 << 30)), N, C, H, W, K, R, S, st, pad, kw, ka,
+                             per_channel=per_channel, with_offset=bool(rng.integers(0, 2)))
+        tag = f"block{block}.{i} N{N} C{C} H{H} W{W} K{K} R{R} S{S} s{st} p{pad} w{kw} a{ka}"
+        print(f"[case] {tag}", flush=True)
+        d = upload(inp, kw, ka, st, pad)
+        pack(d)
+        g = d["g"]
+        geo = (g["N"], g["C"], g["H"], g["W"], g["K"], g["R"], g["S"], st, pad, kw, ka)
+        ref = oracle_mod.conv2d_levels(inp["a"], inp["q"], st, pad)
+        fref = oracle_mod.dequant(ref, inp["scale"], inp["offset"], inp["per_channel"])
+
+        # fused call
+        ebs.ebs_mixed_conv2d(d["pa"], d["pw"], *geo, d["scale"], d["offset"], d["per_channel"], d["acc"], d["out"])
+        torch.cuda.synchronize()
+        assert np.array_equal(d["acc"].cpu().numpy(), ref), tag
+        assert_f32_close(d["out"].cpu().numpy(), fref, ref, inp["scale"], inp["per_channel"])
+
+        # signed weights
+        d["acc"].fill_(POISON)
+        ebs.ebs_mixed_conv2d_signed(d["pa"], d["pw"], *geo, d["scale"], d["offset"], d["per_channel"], d["acc"], None)
+        torch.cuda.synchronize()
+        assert np.array_equal(d["acc"].cpu().numpy(), oracle_mod.conv2d_signed_levels(inp["a"], inp["q"], kw, st, pad)), tag
+
+        # two stages
+        nb = ebs.ebs_partial_products_bytes(N, H, W, K, R, S, st, pad, kw, ka)
+        planes = torch.full((nb // 4,), POISON, dtype=torch.int32, device=d["acc"].device)
+        d["acc"].fill_(POISON)
+        ebs.ebs_binary_conv_planes(d["pa"], d["pw"], *geo, planes)
+        ebs.ebs_pow2_depthwise(planes, g["N"] * g["OH"] * g["OW"], K, kw, ka, d["scale"], d["offset"], d["per_channel"],
+                               d["acc"], d["out"])
+        torch.cuda.synchronize()
+        assert np.array_equal(planes.cpu().numpy().reshape(kw, ka, N, g["OH"], g["OW"], K),
+                              oracle_mod.partial_products(inp["a"], inp["q"], kw, ka, st, pad)), tag
+        assert np.array_equal(d["acc"].cpu().numpy(), ref), tag
+
+        # fused re-quantisation (outputs spread over and beyond the clip range)
+        top = max(1, C * R * S * (2 ** kw - 1) * (2 ** ka - 1))
+        sc = (inp["scale"] * np.float32(40.0 / top)).astype(np.float32)
+        of = (np.zeros_like(sc) if inp["offset"] is None else inp["offset"] * np.float32(5.0)) - np.float32(0.25)
+        k_next, alpha = int(rng.integers(1, 6)), float(rng.choice([6.0, 2.37, 1.0]))
+        nxt = torch.full((ebs.ebs_packed_activations_bytes(N, g["OH"], g["OW"], K, k_next) // 4,), POISON,
+                         dtype=torch.int32, device=d["acc"].device)
+        ebs.ebs_mixed_conv2d_requant(d["pa"], d["pw"], *geo, torch.from_numpy(sc).to(nxt.device),
+                                     torch.from_numpy(of.astype(np.float32)).to(nxt.device), per_channel, alpha, k_next, nxt)
+        torch.cuda.synchronize()
+        want = oracle_mod.requant_levels(ref, sc, of.astype(np.float32), per_channel, alpha, k_next)
+        lv, padbits, border = unpack_activations(nxt.cpu().numpy(), N, g["OH"], g["OW"], K, k_next)
+        assert np.array_equal(lv, want), tag
+        assert not padbits.any() and not border.any(), tag
