@@ -44,6 +44,7 @@ def parse():
     ap.add_argument("--no-requant", action="store_true", help="skip timing the fused re-quantising call")
     ap.add_argument("--no-two-stage", action="store_true", help="skip timing the literal two-stage form")
     ap.add_argument("--no-quantizers", action="store_true", help="skip timing the quantiser / aggregation kernels")
+    ap.add_argument("--no-chain", action="store_true", help="skip timing the chained ResNet-20-shaped stack")
     ap.add_argument("--only", default=None, metavar="LAYER,KW,KA",
                     help="restrict the workload to one case (layer index and bitwidths), e.g. 0,2,2")
     ap.add_argument("--traffic-pass", action="store_true",
@@ -450,6 +451,62 @@ def main():
             "aggregate_weights_5_candidates": {"us": round(t_aw, 2), "gelem_per_s": round(nw / t_aw / 1e3, 2)},
         }
 
+    # ---- NEXT row: the 18 ResNet-20-shaped layers of config 2 as one stack through the fused re-quantising call
+    #      (signed weights, per-channel affine map), eagerly and as a captured HIP graph
+    chain_out = None
+    if not args.no_chain:
+        chain = wl.resnet20_chain(N=128)
+        L0, k0 = chain["layers"][0]["layer"], chain["layers"][0]["k_a"]
+        a0 = torch.from_numpy(chain["a0"]).to(dev)
+        packed = [torch.empty(ebs.ebs_packed_activations_bytes(L0.N, L0.H, L0.W, L0.C, k0) // 4, dtype=torch.int32, device=dev)]
+        pws, scs, ofs = [], [], []
+        for sdef in chain["layers"]:
+            L = sdef["layer"]
+            pw = torch.empty(ebs.ebs_packed_weights_bytes(L.K, L.C, L.R, L.S, sdef["k_w"]) // 4, dtype=torch.int32, device=dev)
+            ebs.ebs_pack_weights(torch.from_numpy(sdef["q"]).to(dev), L.K, L.C, L.R, L.S, sdef["k_w"], pw)
+            pws.append(pw)
+            scs.append(torch.from_numpy(sdef["scale"]).to(dev))
+            ofs.append(torch.from_numpy(sdef["offset"]).to(dev))
+            packed.append(torch.empty(ebs.ebs_packed_activations_bytes(L.N, L.OH, L.OW, L.K, sdef["k_next"]) // 4,
+                                      dtype=torch.int32, device=dev))
+
+        def run_chain(st):
+            ebs.ebs_pack_activations(a0, L0.N, L0.H, L0.W, L0.C, k0, packed[0], st)
+            for i, sdef in enumerate(chain["layers"]):
+                L = sdef["layer"]
+                ebs.ebs_mixed_conv2d_requant(packed[i], pws[i], L.N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad,
+                                             sdef["k_w"], sdef["k_a"], scs[i], ofs[i], True, sdef["alpha"], sdef["k_next"],
+                                             packed[i + 1], st, signed_weights=True)
+
+        def timed_us(f, reps=20):
+            for _ in range(3):
+                f()
+            torch.cuda.synchronize()
+            e0c, e1c = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0c.record(stream)
+            for _ in range(reps):
+                f()
+            e1c.record(stream)
+            torch.cuda.synchronize()
+            return e0c.elapsed_time(e1c) * 1e3 / reps
+
+        t_eager = timed_us(lambda: run_chain(stream))
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(stream)
+        with torch.cuda.graph(graph, stream=side):
+            run_chain(torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        t_graph = timed_us(graph.replay)
+        chain_ops = sum(2 * sdef["layer"].int_macs * sdef["k_w"] * sdef["k_a"] for sdef in chain["layers"])
+        chain_out = {
+            "workload": "configs[1] ResNet-20-shaped stack, N=128, 18 layers chained through ebs_mixed_conv2d_requant "
+                        "(signed weights, per-channel scale/offset), bitwidths drawn per layer from {1..5}",
+            "eager_us": round(t_eager, 1), "graph_us": round(t_graph, 1),
+            "binary_tops_graph": round(chain_ops / t_graph / 1e6, 1),
+            "images_per_s_graph": round(128 / (t_graph * 1e-6), 0),
+        }
+
     traffic = read_traffic(args.workload)
     if traffic is not None:
         roofline["traffic"] = traffic
@@ -473,6 +530,8 @@ def main():
         out["two_stage_comparison"] = two_stage
     if quant is not None:
         out["quantizers"] = quant
+    if chain_out is not None:
+        out["resnet20_chain"] = chain_out
     clocks = gpu_clocks()
     if clocks:
         out["clocks"] = clocks

@@ -205,3 +205,29 @@ def random_case(seed: int, N, C, H, W, K, R, S, stride, pad, k_w, k_a,
     scale = rng.uniform(0.01, 0.2, size=n).astype(np.float32)
     offset = rng.normal(0.0, 0.1, size=n).astype(np.float32) if with_offset else None
     return {"a": a, "q": q, "scale": scale, "offset": offset, "per_channel": per_channel}
+
+
+def resnet20_chain(N: int = 128, seed: int = BASE_SEED + 700000) -> dict:
+    """The ResNet-20-shaped layers of config 2 as ONE stack: layer i's re-quantised output is layer
+    i+1's input (Eq. 1b-1c between the layers), signed weights (Eq. 1a), per-channel scale/offset as
+    a merged batch normalisation would give them.  Returns the first layer's activation levels and,
+    per layer, the weight levels, bitwidths, the next layer's activation bitwidth, alpha and the
+    affine map.  Scales follow a closed-form estimate of the accumulator's spread (independent
+    uniform weight levels, activations around 45 % of their top level) so that the re-quantised
+    levels use their whole range; no arithmetic of the method is involved."""
+    rng = np.random.default_rng(seed)
+    layers = cifar_resnet20_layers(N)
+    bits = [(int(rng.integers(1, 6)), int(rng.integers(1, 6))) for _ in layers]
+    out = {"a0": draw_levels(rng, (N, layers[0].H, layers[0].W, layers[0].C), bits[0][1], "halfnormal"), "layers": []}
+    for i, L in enumerate(layers):
+        k_w, k_a = bits[i]
+        k_next = bits[i + 1][1] if i + 1 < len(layers) else int(rng.integers(1, 6))
+        alpha = 6.0
+        top_w, top_a = (1 << k_w) - 1, (1 << k_a) - 1
+        sigma_w = np.sqrt((top_w * top_w + 2.0 * top_w) / 3.0)
+        spread = np.sqrt(L.C * L.R * L.S) * sigma_w * 0.45 * top_a
+        scale = (alpha / (2.0 * spread) * rng.uniform(0.7, 1.3, L.K)).astype(np.float32)
+        offset = rng.normal(1.0, 0.5, L.K).astype(np.float32)
+        out["layers"].append({"layer": L, "k_w": k_w, "k_a": k_a, "k_next": k_next, "alpha": alpha,
+                              "q": draw_levels(rng, (L.K, L.R, L.S, L.C), k_w), "scale": scale, "offset": offset})
+    return out

@@ -107,9 +107,10 @@ int launch_requant_tiled(const ConvArgs &a)
 {
     const long long positions = (long long)a.N * a.OH * a.OW;
     const int rs = a.R * a.S;
-    int order[3];
+    int order[4];
     int n = 0;
     if (rs > 1 && rs * a.cw >= 64 && positions <= 16384 && a.cw % 4 == 0) order[n++] = 3;
+    if (a.K < 32) order[n++] = 4 + ch_slot(a.cw);      // 32-channel work-groups would be mostly idle
     order[n++] = ch_slot(a.cw);       // preferred chunk size
     order[n++] = 1;                   // single-word chunks: the smallest footprint
     for (int i = 0; i < n; ++i) {

@@ -425,9 +425,12 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
         //      8 channels]; the four pieces of a 32-channel word are then one aligned dword, which the
         //      write-out copies to the packed tensor.  R4: the partial sums of the four waves first meet in
         //      LDS; the work-group owns 8 channels, one byte of each word, which wave 0 stores directly.
+        //      P4 (layers with fewer than 32 output channels): every wave stores the bytes of its own positions.
         //      Every work-group also clears its share of the zero ring.
-        static_assert(!REQ || (MODE == MODE_K4 && KT % 8 == 0 && C::KB % 32 == 0) || (MODE == MODE_R4 && KT == 8 && PIX == 1),
+        static_assert(!REQ || (MODE == MODE_K4 && KT % 8 == 0 && C::KB % 32 == 0) ||
+                          ((MODE == MODE_R4 || MODE == MODE_P4) && KT == 8 && PIX == 1),
                       "re-quantising kernels own whole bytes of the packed words");
+        constexpr bool BYTES = MODE == MODE_R4 || MODE == MODE_P4;    // a wave's 8 channels are one byte of a word
         const int kmax = sh.k_next;
         int32_t sums[PIX][KT];
 #pragma unroll
@@ -484,8 +487,8 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
 #pragma unroll
                     for (int j = 0; j < kMaxBits; ++j) piece[j] |= ((lv >> j) & 1u) << c;
                 }
-                const int row = p * 64 + lane;
-                if constexpr (MODE == MODE_R4) {
+                const int row = wpx * C::TPW + p * 64 + lane;
+                if constexpr (BYTES) {
                     const int t = t_first + row;
                     if (t < sh.total && !EBS_DBG(1)) {
                         const int n = (int)fd_div((uint32_t)t, sh.div_ohow);
@@ -493,10 +496,16 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
                         const int oh = (int)fd_div((uint32_t)rem, sh.div_ow);
                         const int ow = rem - oh * sh.OW;
                         const size_t pos = ((size_t)n * sh.OHn + oh + kActBorder) * sh.OWn + ow + kActBorder;
-                        uint8_t *dstb = reinterpret_cast<uint8_t *>(packed_next + (pos * sh.cwn + (kb0 >> 5)) * kmax) + ((kb0 >> 3) & 3);
+                        const int byte = (kb0 >> 3) & 3;
+                        uint8_t *dstb = reinterpret_cast<uint8_t *>(packed_next + (pos * sh.cwn + (kb0 >> 5)) * kmax) + byte;
+                        const int fill = kb0 + 8 >= sh.K ? 3 - byte : 0;     // the last channel block also clears the rest of its word
 #pragma unroll
-                        for (int j = 0; j < kMaxBits; ++j)
-                            if (j < kmax) dstb[4 * j] = (uint8_t)piece[j];
+                        for (int j = 0; j < kMaxBits; ++j) {
+                            if (j < kmax) {
+                                dstb[4 * j] = (uint8_t)piece[j];
+                                for (int z = 1; z <= fill; ++z) dstb[4 * j + z] = 0;
+                            }
+                        }
                     }
                 } else {
                     uint8_t *dst = pieces + row * C::REQ_ROWB + wk * (KT / 8);
@@ -511,7 +520,7 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
             }
         }
         if (EBS_DBG(1)) return;
-        if constexpr (MODE != MODE_R4) {
+        if constexpr (!BYTES) {
             __syncthreads();
             constexpr int WPB = C::KB / 32;                // packed words of a position this work-group owns
             const int word0 = kb0 >> 5;
@@ -754,7 +763,7 @@ static int launch_cfg(const ConvArgs &a)
     long long tp = C::TP < sh.total ? C::TP : sh.total;
     long long ucap = g.extent_bound(tp);
     long long stage_dwords = (ucap * C::POSW + 3) / 4 * 4;
-    size_t lds_bytes = (size_t)(stage_dwords + ((REQ && MODE != MODE_R4) ? C::REQ_DWORDS : C::OUT_DWORDS)) * sizeof(uint32_t);
+    size_t lds_bytes = (size_t)(stage_dwords + ((REQ && MODE == MODE_K4) ? C::REQ_DWORDS : C::OUT_DWORDS)) * sizeof(uint32_t);
     if (lds_bytes > kMaxLdsBytes || ucap > (1 << 28)) return EBS_ERR_UNSUPPORTED;
     sh.ucap = (int)ucap;
     sh.stage_dwords = (int)stage_dwords;
@@ -764,7 +773,6 @@ static int launch_cfg(const ConvArgs &a)
 
     long long ptiles = ((long long)sh.total + C::TP - 1) / C::TP;
     long long kblocks = ((long long)a.K + C::KB - 1) / C::KB;
-    if (REQ && MODE == MODE_R4) kblocks = 4LL * words_per_pixel(a.K);   // every byte of every packed word has an owner
     long long nblocks = ptiles * kblocks;
     if (nblocks > (1LL << 30)) return EBS_ERR_UNSUPPORTED;
     sh.kblocks = (int)kblocks;
@@ -833,7 +841,8 @@ static int launch_bits(const ConvArgs &a, int v)
 }
 
 // Re-quantising kernels: K4 arrangement with chunk sizes 2 / 1 / 4 (variants 0 / 1 / 2), and the
-// reduction-split arrangement for layers with few positions and a long reduction (variant 3).
+// reduction-split arrangement for layers with few positions and a long reduction (variant 3), and the
+// position-split arrangement with 8-channel work-groups for layers with few output channels (4 / 5 / 6).
 template <int KW, int KA, int FS, bool SGN>
 static int launch_bits_req_sgn(const ConvArgs &a, int v)
 {
@@ -842,6 +851,9 @@ static int launch_bits_req_sgn(const ConvArgs &a, int v)
         case 1: return launch_cfg<KW, KA, 8, 1, MODE_K4, FS, true, SGN>(a);
         case 2: return launch_cfg<KW, KA, 8, 4, MODE_K4, FS, true, SGN>(a);
         case 3: return launch_cfg<KW, KA, 7, 4, MODE_R4, FS, true, SGN>(a);
+        case 4: return launch_cfg<KW, KA, 7, 2, MODE_P4, FS, true, SGN>(a);
+        case 5: return launch_cfg<KW, KA, 7, 1, MODE_P4, FS, true, SGN>(a);
+        case 6: return launch_cfg<KW, KA, 7, 4, MODE_P4, FS, true, SGN>(a);
     }
     return EBS_ERR_UNSUPPORTED;
 }

@@ -1,0 +1,109 @@
+"""A whole stack through the fused re-quantising call: the 18 ResNet-20-shaped layers of config 2 chained
+(layer i writes layer i+1's packed activations; no int32/fp32 tensor and no pack call in between), against
+the oracle chain layer by layer, eagerly and as a captured HIP graph replayed several times."""
+import numpy as np
+import pytest
+
+import ebs_workloads as wl
+import paper_2003_07577_amd as ebs
+from gpu_harness import POISON, unpack_activations
+
+pytestmark = pytest.mark.gpu
+
+
+def _oracle_chain(oracle_mod, chain):
+    a = chain["a0"]
+    levels = []
+    for s in chain["layers"]:
+        L = s["layer"]
+        acc = oracle_mod.conv2d_signed_levels(a, s["q"], s["k_w"], L.stride, L.pad)
+        a = oracle_mod.requant_levels(acc, s["scale"], s["offset"], True, s["alpha"], s["k_next"])
+        levels.append(a)
+    return levels
+
+
+class GpuChain:
+    def __init__(self, chain):
+        import torch
+        dev = torch.device("cuda:0")
+        self.chain = chain
+        L0, k0 = chain["layers"][0]["layer"], chain["layers"][0]["k_a"]
+        self.a0 = torch.from_numpy(chain["a0"]).to(dev)
+        self.packed = [torch.full((ebs.ebs_packed_activations_bytes(L0.N, L0.H, L0.W, L0.C, k0) // 4,), POISON,
+                                  dtype=torch.int32, device=dev)]
+        self.w, self.sc, self.of = [], [], []
+        for s in chain["layers"]:
+            L = s["layer"]
+            q = torch.from_numpy(s["q"]).to(dev)
+            pw = torch.empty(ebs.ebs_packed_weights_bytes(L.K, L.C, L.R, L.S, s["k_w"]) // 4, dtype=torch.int32, device=dev)
+            ebs.ebs_pack_weights(q, L.K, L.C, L.R, L.S, s["k_w"], pw)          # offline
+            self.w.append(pw)
+            self.sc.append(torch.from_numpy(s["scale"]).to(dev))
+            self.of.append(torch.from_numpy(s["offset"]).to(dev))
+            self.packed.append(torch.full((ebs.ebs_packed_activations_bytes(L.N, L.OH, L.OW, L.K, s["k_next"]) // 4,),
+                                          POISON, dtype=torch.int32, device=dev))
+        torch.cuda.synchronize()
+
+    def run(self, stream=None):
+        """Packs the input levels and enqueues the 18 fused calls on `stream`."""
+        L0, k0 = self.chain["layers"][0]["layer"], self.chain["layers"][0]["k_a"]
+        ebs.ebs_pack_activations(self.a0, L0.N, L0.H, L0.W, L0.C, k0, self.packed[0], stream)
+        for i, s in enumerate(self.chain["layers"]):
+            L = s["layer"]
+            ebs.ebs_mixed_conv2d_requant(self.packed[i], self.w[i], L.N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad,
+                                         s["k_w"], s["k_a"], self.sc[i], self.of[i], True, s["alpha"], s["k_next"],
+                                         self.packed[i + 1], stream, signed_weights=True)
+
+    def levels(self, i):
+        s = self.chain["layers"][i]
+        L = s["layer"]
+        return unpack_activations(self.packed[i + 1].cpu().numpy(), L.N, L.OH, L.OW, L.K, s["k_next"])
+
+
+def test_resnet20_shaped_chain_matches_oracle_layer_by_layer(oracle_mod):
+    import torch
+    chain = wl.resnet20_chain(N=128)
+    # consecutive layers must fit: channels, spatial size and activation bitwidth
+    for a, b in zip(chain["layers"][:-1], chain["layers"][1:]):
+        assert (a["layer"].K, a["layer"].OH, a["layer"].OW, a["k_next"]) == (b["layer"].C, b["layer"].H, b["layer"].W, b["k_a"])
+    ref = _oracle_chain(oracle_mod, chain)
+    g = GpuChain(chain)
+    g.run()
+    torch.cuda.synchronize()
+    for i, want in enumerate(ref):
+        lv, padbits, border = g.levels(i)
+        s = chain["layers"][i]
+        print(f"[case] chain layer {i} {s['layer'].name} w{s['k_w']}a{s['k_a']}->a{s['k_next']} "
+              f"levels used {np.unique(want).size}/{2 ** s['k_next']}", flush=True)
+        assert np.array_equal(lv, want), f"layer {i}: {int((lv != want).sum())} of {want.size} levels differ"
+        assert not padbits.any() and not border.any()
+    # the recipe keeps the stack alive: the last layer's levels are not all clipped or all zero
+    last = ref[-1]
+    assert np.unique(last).size >= 2 and 0.02 < (last > 0).mean()
+
+
+def test_chain_as_captured_graph_replays_identically(oracle_mod):
+    """18 kernels per replay, no allocation and no memset node inside the capture; every replay (with eager
+    work and synchronisations in between) must reproduce the eager result."""
+    import torch
+    chain = wl.resnet20_chain(N=16)
+    g = GpuChain(chain)
+    g.run()
+    torch.cuda.synchronize()
+    eager = [t.clone() for t in g.packed]
+    ref_last = _oracle_chain(oracle_mod, chain)[-1]
+    assert np.array_equal(g.levels(len(chain["layers"]) - 1)[0], ref_last)
+
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.graph(graph, stream=side):
+        g.run(torch.cuda.current_stream())
+    for rep in range(4):
+        for t in g.packed:
+            t.fill_(POISON)                        # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for i, (t, want) in enumerate(zip(g.packed, eager)):
+            assert torch.equal(t, want), f"replay {rep}: packed tensor {i} differs from the eager run"
