@@ -46,7 +46,9 @@ typedef enum {
     EBS_ERR_NULL = -1,        /* a required pointer is NULL                         */
     EBS_ERR_BITWIDTH = -2,    /* k_w or k_a outside [1, 5]                          */
     EBS_ERR_SHAPE = -3,       /* non-positive extent, empty output, pad >= filter,
-                                 or a tensor with 2^31 or more elements            */
+                                 a tensor with 2^31 or more elements, or a reduction
+                                 whose largest sum C*R*S*(2^k_w-1)*(2^k_a-1) does
+                                 not fit an int32                                   */
     EBS_ERR_ALIGN = -4,       /* a buffer is not 16-byte aligned                    */
     EBS_ERR_UNSUPPORTED = -5, /* valid request this build has no kernel for         */
     EBS_ERR_HIP = -6,         /* the HIP runtime refused a launch                   */

@@ -53,6 +53,8 @@ static int check_conv(ConvArgs &a, const void *p0, const void *p1, bool need_sca
     a.OW = (a.W + 2 * a.pad - a.S) / a.stride + 1;
     a.cw = words_per_pixel(a.C);
     if ((long long)a.N * a.OH * a.OW * a.K > kMaxElems) return EBS_ERR_SHAPE;
+    // the largest accumulator, C*R*S*(2^k_w - 1)*(2^k_a - 1), must fit an int32
+    if ((long long)a.C * a.R * a.S * ((1 << a.kw) - 1) * ((1 << a.ka) - 1) > kMaxElems) return EBS_ERR_SHAPE;
     if (!aligned16(p0) || !aligned16(p1) || !aligned16(a.acc) || (a.out && !aligned16(a.out)) || !aligned16(a.next))
         return EBS_ERR_ALIGN;
     if ((reinterpret_cast<uintptr_t>(a.scale) & 3u) || (a.offset && (reinterpret_cast<uintptr_t>(a.offset) & 3u)))

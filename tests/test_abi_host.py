@@ -90,6 +90,10 @@ def test_conv_argument_errors(lib):
     for k in (0, 6, -1):
         assert _conv(k_w=k) == E["BITS"]
         assert _conv(k_a=k) == E["BITS"]
+    # accumulators must fit an int32: 2^17 channels x 25 taps x 31 x 31 does not, 15 x 15 does
+    assert _conv(C=1 << 17, H=8, W=8, K=1, R=5, S=5, pad=2, k_w=5, k_a=5) == E["SHAPE"]
+    # (the passing shape is given a misaligned pointer so that the call still ends on the host)
+    assert _conv(C=1 << 17, H=8, W=8, K=1, R=5, S=5, pad=2, k_w=4, k_a=4, packed_act=FAKE + 4) == E["ALIGN"]
     for bad in [dict(N=0), dict(C=0), dict(H=-2), dict(W=0), dict(K=0), dict(R=0), dict(S=0),
                 dict(stride=0), dict(pad=-1), dict(pad=3), dict(H=1, W=1, pad=0),
                 dict(N=1 << 20, H=1 << 10, W=1 << 10)]:
