@@ -8,7 +8,7 @@ fused shift-accumulate and scale/offset epilogue.  Weight packing is done once
 before timing (it is an offline step in the paper's deployment flow, Sec. 4.3).
 All inputs are resident in HBM before the timed region starts.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line (the README lists the fields).
 """
 from __future__ import annotations
 
@@ -339,7 +339,7 @@ def main():
                 if L in per_layer:
                     r["mfma_i8_us"] = round(per_layer[L], 2)
 
-    # ---- NEXT row: fused re-quantise + re-pack epilogue (replaces conv's 8 B/output and the next pack call)
+    # ---- fused re-quantise + re-pack epilogue (replaces conv's 8 B/output and the next pack call)
     requant = None
     if not args.no_requant:
         t_us = 0.0
@@ -366,7 +366,7 @@ def main():
             "vs_pack_plus_conv": round((conv_us_sum + pack_us_sum) / t_us, 3),
         }
 
-    # ---- NEXT row: the literal two-stage form (partial products through memory, then the depthwise
+    # ---- the literal two-stage form (partial products through memory, then the depthwise
     #      power-of-two recombination), timed on the same cases as the fused kernel
     two_stage = None
     if not args.no_two_stage:
@@ -408,7 +408,7 @@ def main():
             "fused_speedup": round((s1_us + s2_us) / conv_us_sum, 3),
         }
 
-    # ---- NEXT row: quantisers (Eq. 1a-1c) and aggregated quantisation functions (Eq. 6-7) on tensors of the
+    # ---- quantisers (Eq. 1a-1c) and aggregated quantisation functions (Eq. 6-7) on tensors of the
     #      workload's largest layer: its input activations and the largest filter bank
     quant = None
     if not args.no_quantizers:
@@ -451,7 +451,7 @@ def main():
             "aggregate_weights_5_candidates": {"us": round(t_aw, 2), "gelem_per_s": round(nw / t_aw / 1e3, 2)},
         }
 
-    # ---- NEXT row: the 18 ResNet-20-shaped layers of config 2 as one stack through the fused re-quantising call
+    # ---- the 18 ResNet-20-shaped layers of config 2 as one stack through the fused re-quantising call
     #      (signed weights, per-channel affine map), eagerly and as a captured HIP graph
     chain_out = None
     if not args.no_chain:
@@ -538,8 +538,6 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cases)
     cases_out = args.cases_out
-    if cases_out is None and os.path.isdir(os.path.join(ROOT, "gpurun_out")):
-        cases_out = os.path.join(ROOT, "gpurun_out", f"bench_cases_{args.workload}.json")
     if cases_out:
         with open(cases_out, "w") as f:
             json.dump(table, f, indent=1)
