@@ -451,60 +451,64 @@ def main():
             "aggregate_weights_5_candidates": {"us": round(t_aw, 2), "gelem_per_s": round(nw / t_aw / 1e3, 2)},
         }
 
-    # ---- the 18 ResNet-20-shaped layers of config 2 as one stack through the fused re-quantising call
-    #      (signed weights, per-channel affine map), eagerly and as a captured HIP graph
+    # ---- whole stacks through the fused re-quantising call (signed weights, per-channel affine map): the 18
+    #      ResNet-20-shaped layers of config 2 and the 16 ResNet-18-shaped 3x3 layers, eagerly and as a HIP graph
     chain_out = None
     if not args.no_chain:
-        chain = wl.resnet20_chain(N=128)
-        L0, k0 = chain["layers"][0]["layer"], chain["layers"][0]["k_a"]
-        a0 = torch.from_numpy(chain["a0"]).to(dev)
-        packed = [torch.empty(ebs.ebs_packed_activations_bytes(L0.N, L0.H, L0.W, L0.C, k0) // 4, dtype=torch.int32, device=dev)]
-        pws, scs, ofs = [], [], []
-        for sdef in chain["layers"]:
-            L = sdef["layer"]
-            pw = torch.empty(ebs.ebs_packed_weights_bytes(L.K, L.C, L.R, L.S, sdef["k_w"]) // 4, dtype=torch.int32, device=dev)
-            ebs.ebs_pack_weights(torch.from_numpy(sdef["q"]).to(dev), L.K, L.C, L.R, L.S, sdef["k_w"], pw)
-            pws.append(pw)
-            scs.append(torch.from_numpy(sdef["scale"]).to(dev))
-            ofs.append(torch.from_numpy(sdef["offset"]).to(dev))
-            packed.append(torch.empty(ebs.ebs_packed_activations_bytes(L.N, L.OH, L.OW, L.K, sdef["k_next"]) // 4,
-                                      dtype=torch.int32, device=dev))
-
-        def run_chain(st):
-            ebs.ebs_pack_activations(a0, L0.N, L0.H, L0.W, L0.C, k0, packed[0], st)
-            for i, sdef in enumerate(chain["layers"]):
+        def time_chain(chain, label):
+            L0, k0 = chain["layers"][0]["layer"], chain["layers"][0]["k_a"]
+            a0 = torch.from_numpy(chain["a0"]).to(dev)
+            packed = [torch.empty(ebs.ebs_packed_activations_bytes(L0.N, L0.H, L0.W, L0.C, k0) // 4, dtype=torch.int32, device=dev)]
+            pws, scs, ofs = [], [], []
+            for sdef in chain["layers"]:
                 L = sdef["layer"]
-                ebs.ebs_mixed_conv2d_requant(packed[i], pws[i], L.N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad,
-                                             sdef["k_w"], sdef["k_a"], scs[i], ofs[i], True, sdef["alpha"], sdef["k_next"],
-                                             packed[i + 1], st, signed_weights=True)
+                pw = torch.empty(ebs.ebs_packed_weights_bytes(L.K, L.C, L.R, L.S, sdef["k_w"]) // 4, dtype=torch.int32, device=dev)
+                ebs.ebs_pack_weights(torch.from_numpy(sdef["q"]).to(dev), L.K, L.C, L.R, L.S, sdef["k_w"], pw)
+                pws.append(pw)
+                scs.append(torch.from_numpy(sdef["scale"]).to(dev))
+                ofs.append(torch.from_numpy(sdef["offset"]).to(dev))
+                packed.append(torch.empty(ebs.ebs_packed_activations_bytes(L.N, L.OH, L.OW, L.K, sdef["k_next"]) // 4,
+                                          dtype=torch.int32, device=dev))
 
-        def timed_us(f, reps=20):
-            for _ in range(3):
-                f()
-            torch.cuda.synchronize()
-            e0c, e1c = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0c.record(stream)
-            for _ in range(reps):
-                f()
-            e1c.record(stream)
-            torch.cuda.synchronize()
-            return e0c.elapsed_time(e1c) * 1e3 / reps
+            def run_chain(st):
+                ebs.ebs_pack_activations(a0, L0.N, L0.H, L0.W, L0.C, k0, packed[0], st)
+                for i, sdef in enumerate(chain["layers"]):
+                    L = sdef["layer"]
+                    ebs.ebs_mixed_conv2d_requant(packed[i], pws[i], L.N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad,
+                                                 sdef["k_w"], sdef["k_a"], scs[i], ofs[i], True, sdef["alpha"], sdef["k_next"],
+                                                 packed[i + 1], st, signed_weights=True)
 
-        t_eager = timed_us(lambda: run_chain(stream))
-        graph = torch.cuda.CUDAGraph()
-        side = torch.cuda.Stream()
-        side.wait_stream(stream)
-        with torch.cuda.graph(graph, stream=side):
-            run_chain(torch.cuda.current_stream())
-        torch.cuda.synchronize()
-        t_graph = timed_us(graph.replay)
-        chain_ops = sum(2 * sdef["layer"].int_macs * sdef["k_w"] * sdef["k_a"] for sdef in chain["layers"])
+            def timed_us(f, reps=20):
+                for _ in range(3):
+                    f()
+                torch.cuda.synchronize()
+                e0c, e1c = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0c.record(stream)
+                for _ in range(reps):
+                    f()
+                e1c.record(stream)
+                torch.cuda.synchronize()
+                return e0c.elapsed_time(e1c) * 1e3 / reps
+
+            t_eager = timed_us(lambda: run_chain(stream))
+            graph = torch.cuda.CUDAGraph()
+            side = torch.cuda.Stream()
+            side.wait_stream(stream)
+            with torch.cuda.graph(graph, stream=side):
+                run_chain(torch.cuda.current_stream())
+            torch.cuda.synchronize()
+            t_graph = timed_us(graph.replay)
+            ops = sum(2 * sdef["layer"].int_macs * sdef["k_w"] * sdef["k_a"] for sdef in chain["layers"])
+            best = min(t_eager, t_graph)
+            return {"workload": label, "layers": len(chain["layers"]), "batch": L0.N,
+                    "bitwidths": [[sdef["k_w"], sdef["k_a"]] for sdef in chain["layers"]],
+                    "eager_us": round(t_eager, 1), "graph_us": round(t_graph, 1),
+                    "binary_tops": round(ops / best / 1e6, 1), "frac_of_alu_roof": round(ops / best / 1e6 / PEAK_BINARY_TOPS, 4),
+                    "images_per_s": round(L0.N / (best * 1e-6), 0)}
+
         chain_out = {
-            "workload": "configs[1] ResNet-20-shaped stack, N=128, 18 layers chained through ebs_mixed_conv2d_requant "
-                        "(signed weights, per-channel scale/offset), bitwidths drawn per layer from {1..5}",
-            "eager_us": round(t_eager, 1), "graph_us": round(t_graph, 1),
-            "binary_tops_graph": round(chain_ops / t_graph / 1e6, 1),
-            "images_per_s_graph": round(128 / (t_graph * 1e-6), 0),
+            "resnet20": time_chain(wl.resnet20_chain(N=128), "configs[1] ResNet-20-shaped stack (CIFAR sizes), bitwidths from {1..5}"),
+            "resnet18": time_chain(wl.resnet18_chain(N=64), "configs[2] ResNet-18-shaped 3x3 stack (ImageNet sizes), bitwidths from {1..4}"),
         }
 
     traffic = read_traffic(args.workload)
@@ -531,7 +535,7 @@ def main():
     if quant is not None:
         out["quantizers"] = quant
     if chain_out is not None:
-        out["resnet20_chain"] = chain_out
+        out["chained_stacks"] = chain_out
     clocks = gpu_clocks()
     if clocks:
         out["clocks"] = clocks

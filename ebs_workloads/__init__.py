@@ -207,21 +207,21 @@ def random_case(seed: int, N, C, H, W, K, R, S, stride, pad, k_w, k_a,
     return {"a": a, "q": q, "scale": scale, "offset": offset, "per_channel": per_channel}
 
 
-def resnet20_chain(N: int = 128, seed: int = BASE_SEED + 700000) -> dict:
-    """The ResNet-20-shaped layers of config 2 as ONE stack: layer i's re-quantised output is layer
-    i+1's input (Eq. 1b-1c between the layers), signed weights (Eq. 1a), per-channel scale/offset as
-    a merged batch normalisation would give them.  Returns the first layer's activation levels and,
-    per layer, the weight levels, bitwidths, the next layer's activation bitwidth, alpha and the
-    affine map.  Scales follow a closed-form estimate of the accumulator's spread (independent
-    uniform weight levels, activations around 45 % of their top level) so that the re-quantised
-    levels use their whole range; no arithmetic of the method is involved."""
+def _chain(layers: List[Layer], seed: int, max_bits: int = 5) -> dict:
+    """A list of layers as ONE stack: layer i's re-quantised output is layer i+1's input (Eq. 1b-1c
+    between the layers), signed weights (Eq. 1a), per-channel scale/offset as a merged batch
+    normalisation would give them.  Returns the first layer's activation levels and, per layer, the
+    weight levels, bitwidths, the next layer's activation bitwidth, alpha and the affine map.
+    Scales follow a closed-form estimate of the accumulator's spread (independent uniform weight
+    levels, activations around 45 % of their top level) so that the re-quantised levels use their
+    whole range; no arithmetic of the method is involved."""
     rng = np.random.default_rng(seed)
-    layers = cifar_resnet20_layers(N)
-    bits = [(int(rng.integers(1, 6)), int(rng.integers(1, 6))) for _ in layers]
-    out = {"a0": draw_levels(rng, (N, layers[0].H, layers[0].W, layers[0].C), bits[0][1], "halfnormal"), "layers": []}
+    bits = [(int(rng.integers(1, max_bits + 1)), int(rng.integers(1, max_bits + 1))) for _ in layers]
+    L0 = layers[0]
+    out = {"a0": draw_levels(rng, (L0.N, L0.H, L0.W, L0.C), bits[0][1], "halfnormal"), "layers": []}
     for i, L in enumerate(layers):
         k_w, k_a = bits[i]
-        k_next = bits[i + 1][1] if i + 1 < len(layers) else int(rng.integers(1, 6))
+        k_next = bits[i + 1][1] if i + 1 < len(layers) else int(rng.integers(1, max_bits + 1))
         alpha = 6.0
         top_w, top_a = (1 << k_w) - 1, (1 << k_a) - 1
         sigma_w = np.sqrt((top_w * top_w + 2.0 * top_w) / 3.0)
@@ -231,3 +231,17 @@ def resnet20_chain(N: int = 128, seed: int = BASE_SEED + 700000) -> dict:
         out["layers"].append({"layer": L, "k_w": k_w, "k_a": k_a, "k_next": k_next, "alpha": alpha,
                               "q": draw_levels(rng, (L.K, L.R, L.S, L.C), k_w), "scale": scale, "offset": offset})
     return out
+
+
+def resnet20_chain(N: int = 128, seed: int = BASE_SEED + 700000) -> dict:
+    """The 18 ResNet-20-shaped layers of config 2 (CIFAR sizes) chained, bitwidths drawn from {1..5}."""
+    return _chain(cifar_resnet20_layers(N), seed)
+
+
+def resnet18_chain(N: int = 64, seed: int = BASE_SEED + 800000) -> dict:
+    """The 3x3 convolutions of an ImageNet ResNet-18 body in network order (four per stage, the
+    first of stages 2-4 with stride 2; shortcuts and the unquantised first/last layers left out),
+    bitwidths drawn from {1..4} as in the headline workload."""
+    L = resnet18_layers(N)          # s1: 64@56, 128@28, 256@14, 512@7; s2: 64->128, 128->256, 256->512
+    order = [L[0]] * 4 + [L[4]] + [L[1]] * 3 + [L[5]] + [L[2]] * 3 + [L[6]] + [L[3]] * 3
+    return _chain(order, seed, max_bits=4)

@@ -1,4 +1,5 @@
-"""A whole stack through the fused re-quantising call: the 18 ResNet-20-shaped layers of config 2 chained
+"""A whole stack through the fused re-quantising call: the 18 ResNet-20-shaped layers of config 2 at N=128 and
+the 16 ResNet-18-shaped 3x3 layers (N=16 here; the full batch is covered layer by layer elsewhere) chained
 (layer i writes layer i+1's packed activations; no int32/fp32 tensor and no pack call in between), against
 the oracle chain layer by layer, eagerly and as a captured HIP graph replayed several times."""
 import numpy as np
@@ -60,9 +61,10 @@ class GpuChain:
         return unpack_activations(self.packed[i + 1].cpu().numpy(), L.N, L.OH, L.OW, L.K, s["k_next"])
 
 
-def test_resnet20_shaped_chain_matches_oracle_layer_by_layer(oracle_mod):
+@pytest.mark.parametrize("which", ["resnet20", "resnet18"])
+def test_chained_stack_matches_oracle_layer_by_layer(oracle_mod, which):
     import torch
-    chain = wl.resnet20_chain(N=128)
+    chain = wl.resnet20_chain(N=128) if which == "resnet20" else wl.resnet18_chain(N=16)
     # consecutive layers must fit: channels, spatial size and activation bitwidth
     for a, b in zip(chain["layers"][:-1], chain["layers"][1:]):
         assert (a["layer"].K, a["layer"].OH, a["layer"].OW, a["k_next"]) == (b["layer"].C, b["layer"].H, b["layer"].W, b["k_a"])
