@@ -22,12 +22,25 @@ FLAGS = [
 ]
 
 
-def sources():
-    return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
+INST = "conv_tiled_inst.hip"      # compiled once per (k_w, k_a, filter specialisation)
 
 
-def _compile(src: str, extra) -> str:
-    obj = os.path.join(OBJDIR, os.path.basename(src)[:-4] + ".o")
+def jobs_list():
+    """(source, object name, extra flags) of every compile job, the long ones first."""
+    jobs = []
+    for kw in range(5, 0, -1):
+        for ka in range(5, 0, -1):
+            for fs in (3, 0):
+                jobs.append((os.path.join(CSRC, INST), f"conv_tiled_w{kw}a{ka}f{fs}.o",
+                             [f"-DEBS_KW={kw}", f"-DEBS_KA={ka}", f"-DEBS_FS={fs}"]))
+    for src in sorted(glob.glob(os.path.join(CSRC, "*.hip"))):
+        if os.path.basename(src) != INST:
+            jobs.append((src, os.path.basename(src)[:-4] + ".o", []))
+    return jobs
+
+
+def _compile(src: str, objname: str, extra) -> str:
+    obj = os.path.join(OBJDIR, objname)
     r = subprocess.run([HIPCC, *FLAGS, *extra, "-c", src, "-o", obj], stderr=subprocess.PIPE, text=True)
     # the host pass does not know the (device-only) packed-fp32 feature switch: harmless, dropped
     noise = "'-packed-fp32-ops' is not a recognized feature"
@@ -42,8 +55,10 @@ def _compile(src: str, extra) -> str:
 def build_library(jobs: int = 8, extra=()) -> str:
     """Compile every .hip under csrc/ for gfx950 and link libebs.so."""
     os.makedirs(OBJDIR, exist_ok=True)
+    for old in glob.glob(os.path.join(OBJDIR, "*.o")):
+        os.remove(old)
     with concurrent.futures.ThreadPoolExecutor(max_workers=jobs) as ex:
-        objs = list(ex.map(lambda s: _compile(s, list(extra)), sources()))
+        objs = list(ex.map(lambda j: _compile(j[0], j[1], j[2] + list(extra)), jobs_list()))
     subprocess.run([HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB, *objs], check=True)
     return LIB
 

@@ -1,20 +1,18 @@
-// Variant table and shape heuristic of the tiled convolution; the kernels are
-// instantiated per (weight bitwidth, filter specialisation) in conv_tiled_kw*_f*.hip.
+// Variant table and shape heuristics of the tiled convolution; the kernels are instantiated per
+// (k_w, k_a, filter specialisation) from conv_tiled_inst.hip.
 #include "ebs_internal.h"
 
 namespace ebs {
 
-template <int KW, int FS> int launch_tiled_kw(const ConvArgs &a, int v);
-template <int KW, int FS> int launch_tiled_req_kw(const ConvArgs &a, int v);
-template <int KW, int FS> int launch_tiled_planes_kw(const ConvArgs &a, int v);
-#define EBS_DECL(kw) \
-    template <> int launch_tiled_planes_kw<kw, 0>(const ConvArgs &a, int v); \
-    template <> int launch_tiled_planes_kw<kw, 3>(const ConvArgs &a, int v); \
-    template <> int launch_tiled_kw<kw, 0>(const ConvArgs &a, int v); \
-    template <> int launch_tiled_kw<kw, 3>(const ConvArgs &a, int v); \
-    template <> int launch_tiled_req_kw<kw, 0>(const ConvArgs &a, int v); \
-    template <> int launch_tiled_req_kw<kw, 3>(const ConvArgs &a, int v);
-EBS_DECL(1) EBS_DECL(2) EBS_DECL(3) EBS_DECL(4) EBS_DECL(5)
+template <int KW, int KA, int FS> int launch_tiled_pair(const ConvArgs &a, int v, int kind);
+#define EBS_PAIRS(X)                                            \
+    X(1, 1) X(1, 2) X(1, 3) X(1, 4) X(1, 5) X(2, 1) X(2, 2) X(2, 3) X(2, 4) X(2, 5) \
+    X(3, 1) X(3, 2) X(3, 3) X(3, 4) X(3, 5) X(4, 1) X(4, 2) X(4, 3) X(4, 4) X(4, 5) \
+    X(5, 1) X(5, 2) X(5, 3) X(5, 4) X(5, 5)
+#define EBS_DECL(kw, ka) \
+    template <> int launch_tiled_pair<kw, ka, 0>(const ConvArgs &a, int v, int kind); \
+    template <> int launch_tiled_pair<kw, ka, 3>(const ConvArgs &a, int v, int kind);
+EBS_PAIRS(EBS_DECL)
 #undef EBS_DECL
 
 // Order must match EBS_TILED_VARIANTS in conv_tiled_kernel.h.
@@ -32,17 +30,20 @@ enum { V_P4_64 = 0, V_P4_32 = 3, V_K4_64 = 6, V_K4_32 = 9, V_K4_16 = 12, V_R4_64
 int conv_tiled_variant_count() { return kNumVariants; }
 const char *conv_tiled_variant_name(int v) { return (v >= 0 && v < kNumVariants) ? kNames[v] : "invalid"; }
 
+// kind 0 = plain convolution, 1 = re-quantising, 2 = plane pairs
+template <int FS>
+static int run_pair(const ConvArgs &a, int v, int kind)
+{
+#define EBS_CASE(kw, ka) case (kw) * 8 + (ka): return launch_tiled_pair<kw, ka, FS>(a, v, kind);
+    switch (a.kw * 8 + a.ka) { EBS_PAIRS(EBS_CASE) }
+#undef EBS_CASE
+    return EBS_ERR_BITWIDTH;
+}
+
 template <int FS>
 static int run_fs(const ConvArgs &a, int v)
 {
-    switch (a.kw) {
-        case 1: return launch_tiled_kw<1, FS>(a, v);
-        case 2: return launch_tiled_kw<2, FS>(a, v);
-        case 3: return launch_tiled_kw<3, FS>(a, v);
-        case 4: return launch_tiled_kw<4, FS>(a, v);
-        case 5: return launch_tiled_kw<5, FS>(a, v);
-    }
-    return EBS_ERR_BITWIDTH;
+    return run_pair<FS>(a, v, 0);
 }
 
 static int run_variant(const ConvArgs &a, int v)
@@ -55,27 +56,13 @@ static int run_variant(const ConvArgs &a, int v)
 template <int FS>
 static int run_req_fs(const ConvArgs &a, int v)
 {
-    switch (a.kw) {
-        case 1: return launch_tiled_req_kw<1, FS>(a, v);
-        case 2: return launch_tiled_req_kw<2, FS>(a, v);
-        case 3: return launch_tiled_req_kw<3, FS>(a, v);
-        case 4: return launch_tiled_req_kw<4, FS>(a, v);
-        case 5: return launch_tiled_req_kw<5, FS>(a, v);
-    }
-    return EBS_ERR_BITWIDTH;
+    return run_pair<FS>(a, v, 1);
 }
 
 template <int FS>
 static int run_planes_fs(const ConvArgs &a, int v)
 {
-    switch (a.kw) {
-        case 1: return launch_tiled_planes_kw<1, FS>(a, v);
-        case 2: return launch_tiled_planes_kw<2, FS>(a, v);
-        case 3: return launch_tiled_planes_kw<3, FS>(a, v);
-        case 4: return launch_tiled_planes_kw<4, FS>(a, v);
-        case 5: return launch_tiled_planes_kw<5, FS>(a, v);
-    }
-    return EBS_ERR_BITWIDTH;
+    return run_pair<FS>(a, v, 2);
 }
 
 // Stage 1 of the two-stage form: four-word chunks when the words per position allow, else single words.
@@ -110,7 +97,7 @@ int launch_requant_tiled(const ConvArgs &a)
     int order[4];
     int n = 0;
     if (rs > 1 && rs * a.cw >= 64 && positions <= 16384 && a.cw % 4 == 0) order[n++] = 3;
-    if (a.K < 32) order[n++] = 4 + ch_slot(a.cw);      // 32-channel work-groups would be mostly idle
+    if (a.K < 32) order[n++] = a.cw % 2 == 0 ? 4 : 5;  // 32-channel work-groups would be mostly idle
     order[n++] = ch_slot(a.cw);       // preferred chunk size
     order[n++] = 1;                   // single-word chunks: the smallest footprint
     for (int i = 0; i < n; ++i) {

@@ -842,7 +842,8 @@ static int launch_bits(const ConvArgs &a, int v)
 
 // Re-quantising kernels: K4 arrangement with chunk sizes 2 / 1 / 4 (variants 0 / 1 / 2), and the
 // reduction-split arrangement for layers with few positions and a long reduction (variant 3), and the
-// position-split arrangement with 8-channel work-groups for layers with few output channels (4 / 5 / 6).
+// position-split arrangement with 8-channel work-groups for layers with few output channels (4 / 5:
+// chunks of 2 / 1 words).
 template <int KW, int KA, int FS, bool SGN>
 static int launch_bits_req_sgn(const ConvArgs &a, int v)
 {
@@ -853,7 +854,6 @@ static int launch_bits_req_sgn(const ConvArgs &a, int v)
         case 3: return launch_cfg<KW, KA, 7, 4, MODE_R4, FS, true, SGN>(a);
         case 4: return launch_cfg<KW, KA, 7, 2, MODE_P4, FS, true, SGN>(a);
         case 5: return launch_cfg<KW, KA, 7, 1, MODE_P4, FS, true, SGN>(a);
-        case 6: return launch_cfg<KW, KA, 7, 4, MODE_P4, FS, true, SGN>(a);
     }
     return EBS_ERR_UNSUPPORTED;
 }
@@ -877,44 +877,19 @@ static int launch_bits_planes(const ConvArgs &a, int v)
     return EBS_ERR_UNSUPPORTED;
 }
 
-// One translation unit per (weight bitwidth, filter specialisation) instantiates these.
-template <int KW, int FS> int launch_tiled_kw(const ConvArgs &a, int v);
-template <int KW, int FS> int launch_tiled_req_kw(const ConvArgs &a, int v);
-template <int KW, int FS> int launch_tiled_planes_kw(const ConvArgs &a, int v);
+// One object file per (k_w, k_a, filter specialisation) instantiates this (conv_tiled_inst.hip, compiled
+// once per triple): kind 0 = plain convolution, 1 = re-quantising, 2 = plane pairs.
+template <int KW, int KA, int FS> int launch_tiled_pair(const ConvArgs &a, int v, int kind);
 
-#define EBS_DEFINE_TILED_KW(KWV, FSV)                                       \
-    template <> int launch_tiled_kw<KWV, FSV>(const ConvArgs &a, int v)     \
-    {                                                                       \
-        switch (a.ka) {                                                     \
-            case 1: return launch_bits<KWV, 1, FSV>(a, v);                  \
-            case 2: return launch_bits<KWV, 2, FSV>(a, v);                  \
-            case 3: return launch_bits<KWV, 3, FSV>(a, v);                  \
-            case 4: return launch_bits<KWV, 4, FSV>(a, v);                  \
-            case 5: return launch_bits<KWV, 5, FSV>(a, v);                  \
-        }                                                                   \
-        return EBS_ERR_BITWIDTH;                                            \
-    }                                                                       \
-    template <> int launch_tiled_req_kw<KWV, FSV>(const ConvArgs &a, int v) \
-    {                                                                       \
-        switch (a.ka) {                                                     \
-            case 1: return launch_bits_req<KWV, 1, FSV>(a, v);              \
-            case 2: return launch_bits_req<KWV, 2, FSV>(a, v);              \
-            case 3: return launch_bits_req<KWV, 3, FSV>(a, v);              \
-            case 4: return launch_bits_req<KWV, 4, FSV>(a, v);              \
-            case 5: return launch_bits_req<KWV, 5, FSV>(a, v);              \
-        }                                                                   \
-        return EBS_ERR_BITWIDTH;                                            \
-    }                                                                       \
-    template <> int launch_tiled_planes_kw<KWV, FSV>(const ConvArgs &a, int v) \
-    {                                                                       \
-        switch (a.ka) {                                                     \
-            case 1: return launch_bits_planes<KWV, 1, FSV>(a, v);           \
-            case 2: return launch_bits_planes<KWV, 2, FSV>(a, v);           \
-            case 3: return launch_bits_planes<KWV, 3, FSV>(a, v);           \
-            case 4: return launch_bits_planes<KWV, 4, FSV>(a, v);           \
-            case 5: return launch_bits_planes<KWV, 5, FSV>(a, v);           \
-        }                                                                   \
-        return EBS_ERR_BITWIDTH;                                            \
+#define EBS_DEFINE_TILED_PAIR(KWV, KAV, FSV)                                              \
+    template <> int launch_tiled_pair<KWV, KAV, FSV>(const ConvArgs &a, int v, int kind)   \
+    {                                                                                      \
+        switch (kind) {                                                                    \
+            case 0: return launch_bits<KWV, KAV, FSV>(a, v);                               \
+            case 1: return launch_bits_req<KWV, KAV, FSV>(a, v);                           \
+            case 2: return launch_bits_planes<KWV, KAV, FSV>(a, v);                        \
+        }                                                                                  \
+        return EBS_ERR_UNSUPPORTED;                                                        \
     }
 
 }  // namespace ebs
