@@ -116,18 +116,19 @@ int launch_conv_tiled(const ConvArgs &a, int variant)
     // layer has that many channels, and split the reduction (R4) when there are few output
     // positions and a long reduction.
     const long long positions = (long long)a.N * a.OH * a.OW;
-    const int ncls = a.kw + a.ka - 1;
     const int slot = ch_slot(a.cw);
-    const int budget = ncls <= 2 ? 16 : 32;
     const int rs = a.R * a.S;
     // GEMM-shaped layers with few rows (a fully-connected layer as a 1x1 convolution): the
     // one-output-per-thread kernel, whose lanes run along the channels, is the faster one.
     if (rs == 1 && positions <= 4096) return EBS_ERR_UNSUPPORTED;
     int order[6];
     int n = 0;
-    if (rs > 1 && rs * a.cw >= 64 && positions <= 16384 && a.cw % 4 == 0) order[n++] = V_R4_16;
-    if (a.K >= 4 * kt_of(budget, a.kw, a.ka)) order[n++] = (budget == 16 ? V_K4_16 : V_K4_32) + slot;
-    else if (a.K >= 4 * kt_of(16, a.kw, a.ka)) order[n++] = V_K4_16 + slot;
+    // reduction split: 8 channels per wave for one-bit weights with 3-4 bit activations (4 would leave too
+    // little arithmetic per step), else the 16-register tiles
+    if (rs > 1 && rs * a.cw >= 64 && positions <= 16384 && a.cw % 4 == 0)
+        order[n++] = (a.kw == 1 && (a.ka == 3 || a.ka == 4)) ? V_R4_32 : V_R4_16;
+    // channel split: the 16-register tiles (interleaved sweeps: never slower than the 32-register ones)
+    if (a.K >= 4 * kt_of(16, a.kw, a.ka)) order[n++] = V_K4_16 + slot;
     order[n++] = V_P4_32 + slot;
     order[n++] = V_P4_32 + 1;       // ch1: smallest staging footprint
     for (int i = 0; i < n; ++i) {

@@ -814,7 +814,7 @@ static int launch_bits(const ConvArgs &a, int v)
             EBS_X(3, 32, 2, MODE_P4)   EBS_X(4, 32, 1, MODE_P4)   EBS_X(5, 32, 4, MODE_P4)
             EBS_X(9, 32, 2, MODE_K4)   EBS_X(10, 32, 1, MODE_K4)  EBS_X(11, 32, 4, MODE_K4)
             EBS_X(12, 16, 2, MODE_K4)  EBS_X(13, 16, 1, MODE_K4)  EBS_X(14, 16, 4, MODE_K4)
-            EBS_X(17, 16, 4, MODE_R4)
+            EBS_X(16, 32, 4, MODE_R4)  EBS_X(17, 16, 4, MODE_R4)
 #undef EBS_X
         }
         return EBS_ERR_UNSUPPORTED;
