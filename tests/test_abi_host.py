@@ -157,3 +157,13 @@ def test_requant_argument_errors(lib):
     assert call(alpha=float("nan")) == -3
     assert call(H=0) == -3
     assert call(nxt=FAKE + 8) == -4
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU; asking for more must end with a message, not with a wrong number."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr and "--gpus 2" in r.stderr
+    assert r.stdout.strip() == ""
