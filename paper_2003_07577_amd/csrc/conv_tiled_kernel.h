@@ -712,6 +712,13 @@ template <> struct TileSel<16, 3, 5> : TileSelA5<3> {};
 template <> struct TileSel<32, 1, 5> : TileSelA5<1> {};
 template <> struct TileSel<32, 2, 5> : TileSelA5<2> {};
 template <> struct TileSel<32, 3, 5> : TileSelA5<3> {};
+// Budget 48 ("wide"): one position per lane, 8 channels per wave (16 for one shift class).  For 1x1 layers with
+// a very short reduction, which are bound by their output writes: a work-group then writes 128-byte pieces of
+// each output row instead of 64-byte ones, and each wave carries twice the arithmetic per set-up.
+template <int KW, int KA> struct TileSel<48, KW, KA> {
+    static constexpr int PIX = 1;
+    static constexpr int KT = (KW + KA - 1 == 1) ? 16 : 8;
+};
 template <int KW, int KA> struct TileSel<4, KW, KA> {
     static constexpr int PIX = 1;
     static constexpr int KT_ACC = KW * KA <= 4 ? 16 : (KW * KA <= 8 ? 8 : 4);
@@ -802,7 +809,9 @@ static int launch_cfg(const ConvArgs &a)
     X(9, 32, 2, MODE_K4)   X(10, 32, 1, MODE_K4)  X(11, 32, 4, MODE_K4)     \
     X(12, 16, 2, MODE_K4)  X(13, 16, 1, MODE_K4)  X(14, 16, 4, MODE_K4)     \
     X(15, 64, 4, MODE_R4)  X(16, 32, 4, MODE_R4)  X(17, 16, 4, MODE_R4)
-constexpr int kNumTiledVariants = 18;
+// variants 18-20 ("wide", budget 48, chunks of 2 / 1 / 4 words) exist for the generic filter only (FS = 0):
+// they serve 1x1 layers with very short reductions
+constexpr int kNumTiledVariants = 21;
 
 template <int KW, int KA, int FS>
 static int launch_bits(const ConvArgs &a, int v)
@@ -835,6 +844,13 @@ static int launch_bits(const ConvArgs &a, int v)
 #define EBS_X(idx, b, ch, mode) case idx: return launch_cfg<KW, KA, b, ch, mode, FS>(a);
             EBS_TILED_VARIANTS(EBS_X)
 #undef EBS_X
+        }
+        if constexpr (FS == 0) {
+            switch (v) {
+                case 18: return launch_cfg<KW, KA, 48, 2, MODE_K4, FS>(a);
+                case 19: return launch_cfg<KW, KA, 48, 1, MODE_K4, FS>(a);
+                case 20: return launch_cfg<KW, KA, 48, 4, MODE_K4, FS>(a);
+            }
         }
         return EBS_ERR_UNSUPPORTED;
     }
