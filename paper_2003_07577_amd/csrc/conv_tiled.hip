@@ -97,7 +97,7 @@ int launch_requant_tiled(const ConvArgs &a)
     const int rs = a.R * a.S;
     int order[4];
     int n = 0;
-    if (rs > 1 && rs * a.cw >= 64 && positions <= 16384 && a.cw % 4 == 0) order[n++] = 3;
+    if ((rs > 1 || a.kw * a.ka <= 2) && rs * a.cw >= 64 && positions <= 16384 && a.cw % 4 == 0) order[n++] = 3;
     if (a.K < 32) order[n++] = a.cw % 2 == 0 ? 4 : 5;  // 32-channel work-groups would be mostly idle
     order[n++] = ch_slot(a.cw);       // preferred chunk size
     order[n++] = 1;                   // single-word chunks: the smallest footprint
@@ -119,14 +119,12 @@ int launch_conv_tiled(const ConvArgs &a, int variant)
     const long long positions = (long long)a.N * a.OH * a.OW;
     const int slot = ch_slot(a.cw);
     const int rs = a.R * a.S;
-    // GEMM-shaped layers with few rows (a fully-connected layer as a 1x1 convolution): the
-    // one-output-per-thread kernel, whose lanes run along the channels, is the faster one.
-    if (rs == 1 && positions <= 4096) return EBS_ERR_UNSUPPORTED;
     int order[7];
     int n = 0;
     // reduction split: 8 channels per wave for one-bit weights with 3-4 bit activations (4 would leave too
     // little arithmetic per step), else the 16-register tiles
-    if (rs > 1 && rs * a.cw >= 64 && positions <= 16384 && a.cw % 4 == 0)
+    // (1x1 filters: only at one or two plane pairs; with more, the channel split is faster)
+    if ((rs > 1 || a.kw * a.ka <= 2) && rs * a.cw >= 64 && positions <= 16384 && a.cw % 4 == 0)
         order[n++] = (a.kw == 1 && (a.ka == 3 || a.ka == 4)) ? V_R4_32 : V_R4_16;
     // 1x1 layers with at most 8 reduction words per output are bound by their output writes: wide tiles
     // (32-channel pieces of each output row) up to 8 plane pairs; measured -15 % on 64->256 @56x56, -2..4 % on 256->64

@@ -76,6 +76,7 @@ struct TiledShape {
     int k_next, OHn, OWn, cwn;     // bordered output grid (OH+2, OW+2), words per position of the next layer
     int ring_total, ring_per_image;  // dwords of the zero ring of the next layer's packed tensor (all images / one)
     int wtop;         // 0: unsigned weight levels; else 2^k_w - 1 (signed weights 2q - wtop, Eq. 1a)
+    int gather;       // 1x1 filter without padding: stage exactly the tile's own positions (no halo, no ring)
     int dbg;          // experiment switches; only read in EBS_EXPERIMENT builds
 };
 
@@ -177,6 +178,9 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
         const int ow = rem - oh * sh.OW;
         return (n * sh.Hp + oh * sh.stride + origin) * sh.Wp + ow * sh.stride + origin;
     };
+    // 1x1 filters read one input position per output: the staged run is then indexed by the position's
+    // number inside the tile, and the zero ring between rows and images is never copied
+    const bool gather = FS == 0 && sh.gather;
     const int u_lo = base_of(t_first);
     int u_hi = base_of(t_last) + (R - 1) * sh.Wp + (S - 1);
     if (u_hi > u_lo + sh.ucap - 1) u_hi = u_lo + sh.ucap - 1;   // never beyond the LDS allocation
@@ -186,7 +190,7 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
     for (int p = 0; p < PIX; ++p) {
         int t = t_first + wpx * C::TPW + p * 64 + lane;
         int tc = t < sh.total ? t : sh.total - 1;
-        my_lds[p] = (base_of(tc) - u_lo) * C::KAP;
+        my_lds[p] = (gather ? tc - t_first : base_of(tc) - u_lo) * C::KAP;
     }
 
     const int xtra_base = sh.ucap * CH * C::KAP;      // start of the fifth-plane region (five-bit activations)
@@ -194,13 +198,14 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
 
     // ---- staging of one reduction chunk: positions [u_lo, u_hi] of the bordered
     //      input are contiguous in memory; copy CH words (x KA planes) of each
-    const int n_stage = (u_hi - u_lo + 1) * CH;
+    const int n_stage = (gather ? t_last - t_first + 1 : u_hi - u_lo + 1) * CH;
     auto stage = [&](int chunk) {
         const unsigned src0 = ((unsigned)u_lo * sh.cw + chunk * CH) * KA;     // dword index, < 2^31
         for (int x = tid; x < n_stage; x += 256) {
             const int u = x / CH;
             const int w = x - u * CH;
-            const uint32_t *src = act + (src0 + ((unsigned)u * sh.cw + w) * KA);
+            const unsigned rel = gather ? (unsigned)(base_of(t_first + u) - u_lo) : (unsigned)u;
+            const uint32_t *src = act + (src0 + (rel * sh.cw + w) * KA);
             uint32_t *dst = lds + (w * sh.ucap + u) * C::KAP;
             if constexpr (KA == 5) {
                 const UVec<4>::type v4 = {src[0], src[1], src[2], src[3]};
@@ -768,7 +773,11 @@ static int launch_cfg(const ConvArgs &a)
 
     TileGeom g{a.H, a.W, a.R, a.S, a.stride, a.pad, a.OH, a.OW, kActBorder};
     long long tp = C::TP < sh.total ? C::TP : sh.total;
-    long long ucap = g.extent_bound(tp);
+    // worth its extra index arithmetic only where the ring is at least as large as the image (tiny images, and
+    // a fully-connected layer given as a 1x1 convolution on 1x1 images): measured -12..35 % there, +8 % on 56x56
+    sh.gather = (FS == 0 && a.R == 1 && a.S == 1 && a.pad == 0 &&
+                 (long long)(a.H + 2 * kActBorder) * (a.W + 2 * kActBorder) >= 2LL * a.H * a.W) ? 1 : 0;
+    long long ucap = sh.gather ? tp : g.extent_bound(tp);
     long long stage_dwords = (ucap * C::POSW + 3) / 4 * 4;
     size_t lds_bytes = (size_t)(stage_dwords + ((REQ && MODE == MODE_K4) ? C::REQ_DWORDS : C::OUT_DWORDS)) * sizeof(uint32_t);
     if (lds_bytes > kMaxLdsBytes || ucap > (1 << 28)) return EBS_ERR_UNSUPPORTED;
