@@ -516,7 +516,9 @@ def main():
         roofline["traffic"] = traffic
 
     out = {
-        "metric": "effective binary TOP/s of mixed-precision conv layers (pack_activations + conv per layer)",
+        "metric": "effective binary TOP/s and latency per mixed-precision conv layer; % of int roofline",
+        "metric_detail": "value = effective binary TOP/s of pack_activations + conv over all cases of the workload; "
+                         "latency per layer = roofline.avg_launch_us; % of the integer roofline = roofline.frac",
         "value": round(value, 2), "unit": "TOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u32 bit-planes, int32 accumulate, fp32 epilogue", "data": "synthetic",
