@@ -29,7 +29,7 @@ def _draw_geometry(rng):
         return N, C, H, W, K, R, S, stride, pad
 
 
-@pytest.mark.parametrize("block", range(6))
+@pytest.mark.parametrize("block", range(12))
 def test_random_shapes_all_entry_points(oracle_mod, block):
     import torch
     rng = np.random.default_rng(4242 + block)
