@@ -234,6 +234,27 @@ def test_mfma_i8_comparison_matches_oracle(oracle_mod):
     # unsupported channel count is an error code, not a crash
     rc = ebs.ebs_mixed_conv2d_mfma_i8(a, q, 1, 16, 4, 4, 8, 3, 3, 1, 1, sc, None, 0, acc, out, None, check=False)
     assert rc == -5
+    # full-size deep layers (few output positions: the reduction is split among work-groups), with and without fp32
+    for c in wl.config_cases(3):
+        if (c.k_w, c.k_a) != (4, 4) or c.layer_index not in (3, 6):
+            continue
+        L = c.layer
+        inp = wl.make_inputs(c)
+        print(f"[case] mfma {c.tag}", flush=True)
+        a = torch.from_numpy(inp["a"]).to(dev)
+        q = torch.from_numpy(inp["q"]).to(dev)
+        sc = torch.from_numpy(inp["scale"]).to(dev)
+        ref = oracle_mod.conv2d_levels(inp["a"], inp["q"], L.stride, L.pad)
+        for want_f32 in (True, False):
+            acc = torch.full((L.N, L.OH, L.OW, L.K), POISON, dtype=torch.int32, device=dev)
+            out = torch.full((L.N, L.OH, L.OW, L.K), float("nan"), dtype=torch.float32, device=dev)
+            ebs.ebs_mixed_conv2d_mfma_i8(a, q, L.N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad, sc, None, False, acc,
+                                         out if want_f32 else None)
+            torch.cuda.synchronize()
+            assert np.array_equal(acc.cpu().numpy(), ref)
+            if want_f32:
+                fref = oracle_mod.dequant(ref, inp["scale"], None, False)
+                assert_f32_close(out.cpu().numpy(), fref, ref, inp["scale"], False)
 
 
 # ------------------------------------------------------------------ measurement probes
