@@ -210,7 +210,7 @@ int ebs_mixed_conv2d_mfma_i8(const uint8_t *act_levels_nhwc, const uint8_t *wgt_
 
 /*
  * Quantisers (Preliminaries, Eq. 1a-1c; round() is round half up) and the aggregated quantisation
- * functions of the bitwidth search (Sec. 3.1).  Element-wise; all pointers are device memory and
+ * functions of the bitwidth search (Sec. 4.1).  Element-wise; all pointers are device memory and
  * 16-byte aligned unless said otherwise; count > 0 elements; nothing is allocated.
  *
  * workspace: EBS_QUANT_WORKSPACE_BYTES bytes of device memory owned by the caller, overwritten by
@@ -224,14 +224,14 @@ int ebs_mixed_conv2d_mfma_i8(const uint8_t *act_levels_nhwc, const uint8_t *wgt_
  * ebs_quantize_activations (Eq. 1b-1c): levels[i] = round((2^k_a - 1) clip(x_i, 0, alpha) / alpha), the
  *   quantised activation is alpha level/(2^k_a - 1).  Single precision in the order of
  *   ebs_mixed_conv2d_requant: z = min(max(x, 0), alpha); level = floor(fmaf(z, (float)(2^k_a - 1)/alpha, 0.5)).
- * ebs_aggregate_weights (Eq. 6; Eq. 9 when gumbel != NULL): w_hat[i] = sum_c coef_c * W_hat^{bits[c]}[i]
+ * ebs_aggregate_weights (Eq. 6; Eq. 8 when gumbel != NULL): w_hat[i] = sum_c coef_c * W_hat^{bits[c]}[i]
  *   with coef = softmax(strengths), or softmax((log softmax(strengths) + gumbel) / tau): ONE meta
  *   weight tensor in, one aggregated tensor out, whatever the number of candidates.
  * ebs_aggregate_activations (Eq. 7, activation factor): x_hat[i] = sum_c coef_c * X_hat^{bits[c]}[i].
  *   bits      : in, HOST, n_bits candidate bitwidths, each in [1, 8]; 1 <= n_bits <= EBS_MAX_CANDIDATES
  *   strengths : in, device, n_bits floats (the learnable strengths r or s)
  *   gumbel    : in, device, n_bits Gumbel(0,1) samples drawn by the caller, or NULL (deterministic search)
- *   tau       : temperature of Eq. 9 (> 0; ignored when gumbel is NULL)
+ *   tau       : temperature of Eq. 8 (> 0; ignored when gumbel is NULL)
  * k_w and k_a may be 1..8 here (a level is one byte); the convolution calls take up to 5.
  * Errors: EBS_ERR_NULL, EBS_ERR_BITWIDTH (a bitwidth outside its range, n_bits outside its range),
  * EBS_ERR_SHAPE (count == 0 or >= 2^40, alpha or tau not positive and finite), EBS_ERR_ALIGN.

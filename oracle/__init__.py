@@ -14,7 +14,7 @@ Two layers:
   decomposition in matrix notation (Sec. 4.3, Eq. 12-15), used on small cases.
 
 * ``quantizers.py`` (numpy, float64): the weight and activation quantisers (Eq. 1a-1c) and the
-  aggregated quantisation functions of the bitwidth search (Eq. 6, 7, 9).
+  aggregated quantisation functions of the bitwidth search (Eq. 6, 7, 8).
 
 Parity status: every function here is pinned by ``tests/test_oracle_pins.py``
 (closed forms, brute force, float64 library convolution, integer matmul,

@@ -1,5 +1,5 @@
 """CPU oracle for the quantisers (Preliminaries, Eq. 1a-1c) and the aggregated quantisation
-functions of the bitwidth search (Sec. 3.1: Eq. 6 for weights, Eq. 7 for activations, Eq. 9 for
+functions of the bitwidth search (Sec. 4.1: Eq. 6 for weights, Eq. 7 for activations, Eq. 8 for
 the stochastic coefficients).  TEST INFRASTRUCTURE ONLY, like the rest of this package.
 
 Plain numpy in float64, each function the formula as written.  The one exception is the
@@ -11,7 +11,7 @@ Readings of the paper (it is silent or garbled on these):
 * round() is round half up: floor(v + 0.5) (stated below Eq. 1c).
 * all-zero weights: max|tanh W| = 0 makes Eq. 1a 0/0; the normalised value is taken as 0, i.e.
   every weight sits at 1/2 before rounding.
-* Eq. 9 as printed has the division by tau outside exp(); the Gumbel-softmax it cites divides
+* Eq. 8 as printed has the division by tau outside exp(); the Gumbel-softmax it cites divides
   the logits: coefficient_i = exp((log p_i + g_i)/tau) / sum_j exp((log p_j + g_j)/tau).
 """
 from __future__ import annotations
@@ -75,7 +75,7 @@ def softmax(r):
 
 
 def gumbel_softmax(r, g, tau: float):
-    """Eq. 9: p = softmax(r); coefficient_i = exp((log p_i + g_i)/tau) / sum_j exp((log p_j + g_j)/tau),
+    """Eq. 8: p = softmax(r); coefficient_i = exp((log p_i + g_i)/tau) / sum_j exp((log p_j + g_j)/tau),
     g the Gumbel(0,1) samples (an input: the caller draws them)."""
     p = softmax(r)
     y = (np.log(p) + np.asarray(g, dtype=np.float64)) / tau
@@ -88,7 +88,7 @@ def _coefficients(strengths, gumbel, tau):
 
 
 def aggregate_weights(W, bits, strengths, gumbel=None, tau: float = 1.0):
-    """Eq. 6 (Eq. 9 with gumbel): sum_i coefficient_i * W_hat^{b_i}, one meta weight tensor."""
+    """Eq. 6 (Eq. 8 with gumbel): sum_i coefficient_i * W_hat^{b_i}, one meta weight tensor."""
     c = _coefficients(strengths, gumbel, tau)
     out = np.zeros(np.shape(W), dtype=np.float64)
     for ci, b in zip(c, bits):

@@ -14,7 +14,7 @@ constexpr int kWgtGroup = 16;
 // Largest bitwidth of weights and activations: the search space of the paper is {1, ..., 5}
 // (Sec. 5, implementation details).
 constexpr int kMaxBits = 5;
-// Candidate bitwidths of one aggregated quantisation function (Sec. 3.1); the paper searches five.
+// Candidate bitwidths of one aggregated quantisation function (Sec. 4.1); the paper searches five.
 constexpr int kMaxCandidates = EBS_MAX_CANDIDATES;
 
 struct ConvArgs {

@@ -1,5 +1,5 @@
 // Quantisers (paper Preliminaries, Eq. 1a-1c) and the aggregated quantisation functions of
-// the bitwidth search (Sec. 3.1: Eq. 6 weights, Eq. 7 activations, Eq. 9 stochastic
+// the bitwidth search (Sec. 4.1: Eq. 6 weights, Eq. 7 activations, Eq. 8 stochastic
 // coefficients).  All element-wise and HBM-bound, apart from one max reduction.
 //
 // Weights (Eq. 1a) are evaluated in double precision: a rounding decides an integer level, a
@@ -93,7 +93,7 @@ quantize_activations_kernel(const float *__restrict__ x, size_t count, float alp
 }
 
 // Coefficients of the candidates: softmax of the strengths (Eq. 6-7), or with Gumbel noise g and
-// temperature tau the softmax of (log p + g) / tau (Eq. 9).  One thread; at most eight candidates.
+// temperature tau the softmax of (log p + g) / tau (Eq. 8).  One thread; at most eight candidates.
 __global__ void coefficients_kernel(const float *__restrict__ strengths, const float *__restrict__ gumbel, double tau,
                                     const Candidates cand, double alpha, uint8_t *__restrict__ ws)
 {

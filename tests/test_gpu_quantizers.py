@@ -1,5 +1,5 @@
 """GPU parity of the quantisers (Eq. 1a-1c) and the aggregated quantisation functions of the
-bitwidth search (Eq. 6, 7, 9) against the float64 / fixed-order oracle.
+bitwidth search (Eq. 6, 7, 8) against the float64 / fixed-order oracle.
 
 Integer levels must be equal.  For the weight quantiser both sides evaluate Eq. 1a in double
 precision with their own tanh, so a level may differ only where (2^b - 1) x + 1/2 lies within

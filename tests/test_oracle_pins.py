@@ -412,7 +412,7 @@ def test_partial_products_match_bitwise_and_matrix_forms(oracle_mod, kw, ka):
 
 
 
-# ---------------------------------------------------------------- quantisers (Eq. 1a-1c) and aggregation (Eq. 6, 7, 9)
+# ---------------------------------------------------------------- quantisers (Eq. 1a-1c) and aggregation (Eq. 6, 7, 8)
 def test_weight_quantiser_hand_fixture(oracle_mod):
     g = read_sections("quantizer_examples.txt")
     W = np.arctanh(g["tanh_tenths"][0] / 10.0)
