@@ -251,6 +251,24 @@ int ebs_aggregate_activations(const float *x, size_t count, float alpha,
                               float *x_hat, void *workspace, void *stream);
 
 /*
+ * ebs_quantize_weights for callers that cannot allocate device memory and therefore have no
+ * workspace to pass: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same kernels and the same levels as ebs_quantize_weights; the 256-byte workspace is
+ * a device array inside the library (EBS_QUANT_WORKSPACE_BYTES per GPU, held until the process
+ * ends).  The call allocates and frees nothing and records no memset: the word that must start at
+ * zero is cleared by a kernel of the call.
+ *   - count must not exceed EBS_STATIC_MAX_COUNT (EBS_ERR_SHAPE otherwise; the workspace itself
+ *     does not grow with count, the bound is what one launch of the element-wise kernel covers).
+ *   - The device that owns `stream` must be the current device of the calling thread.
+ *   - Every call on one GPU shares that GPU's array: calls that may overlap on one GPU (different
+ *     streams, different threads) race on it and must be ordered by the caller.
+ *   - More than 64 devices in one process: EBS_ERR_UNSUPPORTED.
+ * Other arguments and error codes as for ebs_quantize_weights.
+ */
+#define EBS_STATIC_MAX_COUNT (1ull << 31)
+int ebs_quantize_weights_static(const float *w, size_t count, int k_w, uint8_t *levels, void *stream);
+
+/*
  * Debug aid: *device_flag (int32 on the device, cleared by this call) becomes
  * non-zero if any of `count` levels is >= 2^bits.  The pack calls themselves
  * never fail on range; they keep the low bits.

@@ -15,6 +15,8 @@ from .binding import (  # noqa: F401
     ebs_mixed_conv2d_signed,
     ebs_partial_products_bytes,
     ebs_quantize_weights,
+    ebs_quantize_weights_static,
+    STATIC_MAX_COUNT,
     ebs_quantize_activations,
     ebs_aggregate_weights,
     ebs_aggregate_activations,

@@ -76,6 +76,8 @@ def load_library():
         _sz, _fl = ctypes.c_size_t, ctypes.c_float
         lib.ebs_quantize_weights.restype = _ci
         lib.ebs_quantize_weights.argtypes = [_vp, _sz, _ci, _vp, _vp, _vp]
+        lib.ebs_quantize_weights_static.restype = _ci
+        lib.ebs_quantize_weights_static.argtypes = [_vp, _sz, _ci, _vp, _vp]
         lib.ebs_quantize_activations.restype = _ci
         lib.ebs_quantize_activations.argtypes = [_vp, _sz, _fl, _ci, _vp, _vp]
         lib.ebs_aggregate_weights.restype = _ci
@@ -204,6 +206,7 @@ def ebs_pow2_depthwise(planes, positions, K, k_w, k_a, scale, offset, per_channe
 
 
 QUANT_WORKSPACE_BYTES = 256     # EBS_QUANT_WORKSPACE_BYTES
+STATIC_MAX_COUNT = 1 << 31      # EBS_STATIC_MAX_COUNT
 MAX_CANDIDATES = 8              # EBS_MAX_CANDIDATES
 
 
@@ -216,6 +219,13 @@ def ebs_quantize_weights(w, count, k_w, levels, workspace, stream=None, check=Tr
     rc = load_library().ebs_quantize_weights(_ptr(w), count, k_w, _ptr(levels), _ptr(workspace), _stream(stream))
     if check:
         _check(rc, "ebs_quantize_weights")
+    return rc
+
+
+def ebs_quantize_weights_static(w, count, k_w, levels, stream=None, check=True) -> int:
+    rc = load_library().ebs_quantize_weights_static(_ptr(w), count, k_w, _ptr(levels), _stream(stream))
+    if check:
+        _check(rc, "ebs_quantize_weights_static")
     return rc
 
 

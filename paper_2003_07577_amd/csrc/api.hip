@@ -300,6 +300,15 @@ int ebs_quantize_weights(const float *w, size_t count, int k_w, uint8_t *levels,
     return quantize_weights(w, count, k_w, levels, workspace, (hipStream_t)stream);
 }
 
+int ebs_quantize_weights_static(const float *w, size_t count, int k_w, uint8_t *levels, void *stream)
+{
+    int rc = check_elementwise(w, levels, count);
+    if (rc) return rc;
+    if (count > (size_t)EBS_STATIC_MAX_COUNT) return EBS_ERR_SHAPE;
+    if (k_w < 1 || k_w > 8) return EBS_ERR_BITWIDTH;
+    return quantize_weights_static(w, count, k_w, levels, (hipStream_t)stream);
+}
+
 int ebs_quantize_activations(const float *x, size_t count, float alpha, int k_a, uint8_t *levels, void *stream)
 {
     int rc = check_elementwise(x, levels, count);

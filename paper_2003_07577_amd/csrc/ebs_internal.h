@@ -61,6 +61,7 @@ int launch_pow2_depthwise(const int32_t *planes, long long plane_elems, int K, i
                           const float *offset, int per_channel, int32_t *acc, float *out, hipStream_t st);
 // Quantisers and aggregated quantisation functions (quantize.hip); workspace: 256 device bytes.
 int quantize_weights(const float *w, size_t count, int bits, uint8_t *levels, void *workspace, hipStream_t st);
+int quantize_weights_static(const float *w, size_t count, int bits, uint8_t *levels, hipStream_t st);
 int quantize_activations(const float *x, size_t count, float alpha, int bits, uint8_t *levels, hipStream_t st);
 int aggregate_weights(const float *w, size_t count, const int *bits, int n, const float *strengths, const float *gumbel,
                       float tau, float *out, void *workspace, hipStream_t st);

@@ -14,8 +14,38 @@
 // coefficient_i * alpha / (2^b_i - 1).
 #include "ebs_internal.h"
 #include "requant.h"
+#include <mutex>
 
 namespace ebs {
+
+// Workspace of ebs_quantize_weights_static: the same 256 bytes the caller of ebs_quantize_weights
+// brings in, here a device array of the library itself (one copy per GPU, at an address of its
+// own on each; held until the process ends).  Host code never uses the array's name as a
+// pointer: the address on the current device comes from hipGetSymbolAddress, once per device.
+static __device__ __align__(256) unsigned char scratch[EBS_QUANT_WORKSPACE_BYTES];
+
+constexpr int kMaxDevices = 64;
+
+// Address of `scratch` on the current device (looked up on the first call per device, kept after).
+static int static_workspace(void **out)
+{
+    static std::mutex mu;
+    static void *ptrs[kMaxDevices] = {};
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_ok(e);
+    if (dev < 0 || dev >= kMaxDevices) return EBS_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptrs[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return hip_ok(e);
+        if (!p) return EBS_ERR_HIP;
+        ptrs[dev] = p;
+    }
+    *out = ptrs[dev];
+    return EBS_OK;
+}
 
 struct Candidates {
     int n;
@@ -186,6 +216,16 @@ int quantize_weights(const float *w, size_t count, int bits, uint8_t *levels, vo
     if (rc) return rc;
     hipLaunchKernelGGL(quantize_weights_kernel, dim3(blocks_for(count)), dim3(256), 0, st, w, count, (1 << bits) - 1, ws, levels);
     return hip_ok(hipGetLastError());
+}
+
+// Same kernels as quantize_weights, the workspace being the library's own device array: no allocation
+// anywhere (the first kernel clears the one word that must start at zero).
+int quantize_weights_static(const float *w, size_t count, int bits, uint8_t *levels, hipStream_t st)
+{
+    void *ws = nullptr;
+    int rc = static_workspace(&ws);
+    if (rc) return rc;
+    return quantize_weights(w, count, bits, levels, ws, st);
 }
 
 int quantize_activations(const float *x, size_t count, float alpha, int bits, uint8_t *levels, hipStream_t st)
