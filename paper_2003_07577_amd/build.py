@@ -23,6 +23,7 @@ FLAGS = [
 
 
 INST = "conv_tiled_inst.hip"      # compiled once per (k_w, k_a, filter specialisation)
+LANE_INST = "conv_lane_inst.hip"  # compiled once per (k_w, k_a), bitwidths up to 4
 
 
 def jobs_list():
@@ -33,8 +34,11 @@ def jobs_list():
             for fs in (3, 0):
                 jobs.append((os.path.join(CSRC, INST), f"conv_tiled_w{kw}a{ka}f{fs}.o",
                              [f"-DEBS_KW={kw}", f"-DEBS_KA={ka}", f"-DEBS_FS={fs}"]))
+    for kw in range(4, 0, -1):
+        for ka in range(4, 0, -1):
+            jobs.append((os.path.join(CSRC, LANE_INST), f"conv_lane_w{kw}a{ka}.o", [f"-DEBS_KW={kw}", f"-DEBS_KA={ka}"]))
     for src in sorted(glob.glob(os.path.join(CSRC, "*.hip"))):
-        if os.path.basename(src) != INST:
+        if os.path.basename(src) not in (INST, LANE_INST):
             jobs.append((src, os.path.basename(src)[:-4] + ".o", []))
     return jobs
 
@@ -64,5 +68,5 @@ def build_library(jobs: int = 8, extra=()) -> str:
 
 
 if __name__ == "__main__":
-    # EBS_BUILD_EXTRA="-DEBS_EXPERIMENT" builds the phase-timing experiment variant
+    # EBS_BUILD_EXTRA: extra compiler flags for every translation unit
     print(build_library(extra=tuple(os.environ.get("EBS_BUILD_EXTRA", "").split())))

@@ -267,7 +267,7 @@ int ebs_mixed_conv2d_requant(const void *packed_act, const void *packed_wgt,
     a.wtop = signed_weights ? (1 << k_w) - 1 : 0;
     rc = launch_requant_tiled(a);                     // writes the zero ring itself
     if (rc != EBS_ERR_UNSUPPORTED) return rc;
-    rc = launch_zero_border(a.next, N, a.OH, a.OW, words_per_pixel(K) * k_next, a.stream);
+    rc = launch_zero_border(a.next, N, a.OH, a.OW, words_per_pixel(K), k_next, a.stream);
     if (rc) return rc;
     return launch_requant_naive(a);
 }

@@ -1,0 +1,245 @@
+// AND + bitcount convolution, "channel per lane" arrangement, for 3x3 filters (paper Sec. 3
+// Eq. 2; Sec. 4.3 Eq. 13-14 fused into one kernel as in the tiled kernel: the bit-plane partial
+// products stay in registers, one accumulator per shift class i+j).
+//
+// Mapping (CDNA4, 64-wide waves).  The waves of a work-group are independent: no LDS, no barrier.
+//  * a lane owns ONE output channel; a wave owns 64 consecutive channels x a run of P consecutive
+//    output positions of one output row (a "tile").
+//  * activation words are wave-uniform.  The packed input is [word][position][plane] over the
+//    zero-bordered grid, so the (P-1)*stride + 3 input positions that one filter row of the run
+//    touches are, for one reduction word, ONE contiguous piece of memory: it is fetched with
+//    scalar loads and its words are the scalar operands of v_and_b32.  Weight words are per-lane
+//    vector loads (one load brings the k_w planes of the lane's channel) and are reused for the P
+//    positions.  Inner body per (word, plane pair, position): v_and_b32 v, s, v + accumulating
+//    v_bcnt_u32_b32, as in the tiled kernel.
+//  * everything about positions is wave-uniform and runs on the scalar unit; a wave stores 256
+//    consecutive bytes of an NHWC output row per position straight from its accumulators.
+//  * a reduction step is (filter row r, word w); the operands of the next step are requested
+//    before the current step is multiplied.  The loop body is one block of instructions (offsets
+//    advance by selects, not branches), which keeps the requests where they are written.
+#pragma once
+#include "ebs_internal.h"
+#include "fastdiv.h"
+
+namespace ebs {
+
+struct LaneShape {
+    int K, cw, OH, OW;
+    int Wp;             // bordered row length (W + 2)
+    int plane_pos;      // bordered positions per image (H + 2) * (W + 2)
+    int total_pos;      // N * plane_pos: positions per word of the packed input
+    int origin;         // border - pad
+    int runs;           // runs of P positions per output row
+    int kgroups;        // ceil(K / 64)
+    int ntiles;         // N*OH * runs * kgroups
+    int xcd_chunk;      // ceil(work-groups / 8): work-groups of one die
+    int per_channel;
+    FastDiv div_kgroups, div_runs, div_oh;
+};
+
+__device__ __forceinline__ uint32_t lane_bcnt_acc(uint32_t x, uint32_t acc)
+{
+    uint32_t d;
+    asm("v_bcnt_u32_b32 %0, %1, %2" : "=v"(d) : "v"(x), "v"(acc));
+    return d;
+}
+
+__device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
+template <int KW, int KA, int P, int ST>
+__global__ void __launch_bounds__(256)
+bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
+             const float *__restrict__ scale, const float *__restrict__ offset,
+             int32_t *__restrict__ acc_out, float *__restrict__ out_f32, const LaneShape sh)
+{
+    constexpr int NCLS = KW + KA - 1;
+    constexpr int NSEG = (P - 1) * ST + 3;        // input positions one filter row of the run touches
+    constexpr int XN = NSEG * KA;                 // dwords of one step's input piece
+    constexpr int FS = 3;
+    constexpr int QSTEP = kWgtGroup * KW;         // weights [k/16][tap][word][k%16][plane]: dwords per (tap, word)
+
+    // ---- this wave's tile: dies take contiguous runs of work-groups (work-groups are dealt to the dies
+    //      round-robin), a work-group four consecutive tiles; everything here is wave-uniform
+    const unsigned lane = threadIdx.x & 63;
+    const unsigned lane4 = lane * 4u;
+    const int wave = uni(threadIdx.x >> 6);
+    const int wgi = (int)(blockIdx.x & 7) * sh.xcd_chunk + (int)(blockIdx.x >> 3);
+    const int tile = wgi * 4 + wave;
+    if ((int)(blockIdx.x >> 3) >= sh.xcd_chunk || tile >= sh.ntiles) return;
+    const int ptile = (int)fd_div((uint32_t)tile, sh.div_kgroups);
+    const int kg = tile - ptile * sh.kgroups;
+    const int grow = (int)fd_div((uint32_t)ptile, sh.div_runs);       // n*OH + oh
+    const int run = ptile - grow * sh.runs;
+    const int n = (int)fd_div((uint32_t)grow, sh.div_oh);
+    const int oh = grow - n * sh.OH;
+    int ow0 = run * P;
+    if (ow0 > sh.OW - P) ow0 = sh.OW - P;         // the last run of a row is moved left; the overlap is computed twice
+
+    const int k = kg * 64 + (int)lane;
+    const int kc = k < sh.K ? k : sh.K - 1;
+    // byte offset of the lane's channel in the packed weights
+    const unsigned qlane = (unsigned)(((kc / kWgtGroup) * (FS * FS) * sh.cw * kWgtGroup + (kc % kWgtGroup)) * KW) * 4u;
+    const int ci = sh.per_channel ? kc : 0;
+    const float sc = scale[ci];
+    const float of = offset ? offset[ci] : 0.0f;
+
+    // ---- the reduction: steps (filter row r, word w), w fastest.  Offsets of a step's operands (dwords):
+    unsigned x_off = (unsigned)uni((n * sh.plane_pos + (oh * ST + sh.origin) * sh.Wp + ow0 * ST + sh.origin) * KA);
+    unsigned q_off = 0;
+    const unsigned x_wstep = (unsigned)sh.total_pos * KA;                       // next word
+    const unsigned x_rwrap = (unsigned)sh.Wp * KA - (unsigned)(sh.cw - 1) * x_wstep;   // first word of the next filter row
+    const unsigned q_rwrap = (unsigned)((FS - 1) * sh.cw * QSTEP + QSTEP);
+    const unsigned q_tap = (unsigned)(sh.cw * QSTEP);
+    int w_next = 0;                               // word index of the step the offsets point at
+    int left = FS * sh.cw;                        // steps not yet requested
+    // request the operands of the step the offsets point at (one scalar piece of input, one per-lane load per
+    // tap that brings the k_w planes), then move the offsets one step on - without a branch, so that the loop
+    // body stays one block of instructions; past the last step the offsets stay where they are
+    auto issue = [&](uint32_t (&x)[XN], uint32_t (&q)[FS][KW]) {
+        const uint32_t *xs = act + x_off;         // wave-uniform address: scalar loads
+#pragma unroll
+        for (int e = 0; e < XN; ++e) x[e] = xs[e];
+#pragma unroll
+        for (int s = 0; s < FS; ++s) {
+            const char *qt = reinterpret_cast<const char *>(wgt + (q_off + (unsigned)s * q_tap));
+            typedef uint32_t qvec __attribute__((ext_vector_type(KW), aligned(4)));
+            if constexpr (KW == 1) {
+                q[s][0] = *reinterpret_cast<const uint32_t *>(qt + qlane);
+            } else {
+                const qvec v = *reinterpret_cast<const qvec *>(qt + qlane);
+#pragma unroll
+                for (int i = 0; i < KW; ++i) q[s][i] = v[i];
+            }
+        }
+        const bool more = --left > 0;
+        const bool wrap = w_next + 1 == sh.cw;
+        w_next = wrap ? 0 : w_next + 1;
+        x_off += more ? (wrap ? x_rwrap : x_wstep) : 0u;
+        q_off += more ? (wrap ? q_rwrap : (unsigned)QSTEP) : 0u;
+    };
+
+    uint32_t cls[P][NCLS];
+#pragma unroll
+    for (int p = 0; p < P; ++p)
+#pragma unroll
+        for (int c = 0; c < NCLS; ++c) cls[p][c] = 0u;
+    // Eq. 2 / Eq. 13 on one (filter row, word): the three taps of the row for the P positions
+    auto mac = [&](const uint32_t (&x)[XN], const uint32_t (&q)[FS][KW]) {
+#pragma unroll
+        for (int s = 0; s < FS; ++s)
+#pragma unroll
+            for (int p = 0; p < P; ++p)
+#pragma unroll
+                for (int i = 0; i < KW; ++i)
+#pragma unroll
+                    for (int j = 0; j < KA; ++j)
+                        cls[p][i + j] = lane_bcnt_acc(q[s][i] & x[(p * ST + s) * KA + j], cls[p][i + j]);
+    };
+
+    // two steps per trip (the number of steps, 3 * words, is even for an even number of words; the launcher
+    // sends other shapes elsewhere); each step's operands are requested one step ahead
+    uint32_t xa[XN], xb[XN], qa[FS][KW], qb[FS][KW];
+    issue(xa, qa);
+    const int trips = (FS * sh.cw) >> 1;
+    // Scalar loads can only be waited for all at once.  A step therefore first waits for its own input piece
+    // (requested one step ago), then requests the next step's, then multiplies: the wait the multiplication needs
+    // would otherwise also cover the request just made.
+    for (int t = 0; t < trips; ++t) {
+        __builtin_amdgcn_s_waitcnt(0xC07F);       // lgkmcnt(0)
+        __builtin_amdgcn_sched_barrier(0);
+        issue(xb, qb);
+        __builtin_amdgcn_sched_barrier(0);
+        mac(xa, qa);
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_waitcnt(0xC07F);
+        __builtin_amdgcn_sched_barrier(0);
+        issue(xa, qa);                            // (the last trip re-requests the last step: never used)
+        __builtin_amdgcn_sched_barrier(0);
+        mac(xb, qb);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+
+    // ---- Eq. 14 and the affine epilogue; per position a wave writes 64 consecutive values
+    if (k < sh.K) {
+        int32_t acc[P];
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            uint32_t v = 0;
+#pragma unroll
+            for (int c = 0; c < NCLS; ++c) v += cls[p][c] << c;
+            acc[p] = (int32_t)v;
+        }
+        const size_t o0 = ((size_t)grow * sh.OW + ow0) * sh.K + (size_t)(kg * 64);
+        char *dst_i = reinterpret_cast<char *>(acc_out + o0);
+#pragma unroll
+        for (int p = 0; p < P; ++p)
+            *reinterpret_cast<int32_t *>(dst_i + (size_t)(p * sh.K) * 4 + lane4) = acc[p];
+        if (out_f32) {
+            char *dst_f = reinterpret_cast<char *>(out_f32 + o0);
+#pragma unroll
+            for (int p = 0; p < P; ++p)
+                *reinterpret_cast<float *>(dst_f + (size_t)(p * sh.K) * 4 + lane4) = fmaf((float)acc[p], sc, of);
+        }
+    }
+}
+
+// Positions per run: the large choice where accumulators (P * shift classes) and the scalar registers of the
+// input pieces (two buffers of ((P-1)*stride + 3) * k_a) allow it, and a small one for narrow rows.
+template <int KW, int KA, int ST> struct LaneRun {
+    static constexpr int NCLS = KW + KA - 1;
+    static constexpr int BIG = ST == 1 ? ((KA <= 2 && NCLS <= 4) ? 14 : 7) : (KA <= 2 ? 7 : 4);
+    static constexpr int SMALL = ST == 1 ? 7 : 4;
+};
+
+template <int KW, int KA, int P, int ST>
+static int launch_lane_cfg(const ConvArgs &a)
+{
+    if (a.wtop || a.next) return EBS_ERR_UNSUPPORTED;
+    if (a.R != 3 || a.S != 3 || a.stride != ST || a.pad > kActBorder || a.OW < P || (a.cw & 1)) return EBS_ERR_UNSUPPORTED;
+    LaneShape sh{};
+    sh.K = a.K; sh.cw = a.cw; sh.OH = a.OH; sh.OW = a.OW;
+    sh.Wp = a.W + 2 * kActBorder;
+    sh.plane_pos = (a.H + 2 * kActBorder) * sh.Wp;
+    sh.total_pos = a.N * sh.plane_pos;
+    sh.origin = kActBorder - a.pad;
+    sh.runs = (a.OW + P - 1) / P;
+    sh.kgroups = (a.K + 63) / 64;
+    long long ntiles = (long long)a.N * a.OH * sh.runs * sh.kgroups;
+    if (ntiles > (1LL << 30)) return EBS_ERR_UNSUPPORTED;
+    sh.ntiles = (int)ntiles;
+    sh.per_channel = a.per_channel;
+    sh.div_kgroups = make_fastdiv((uint32_t)sh.kgroups);
+    sh.div_runs = make_fastdiv((uint32_t)sh.runs);
+    sh.div_oh = make_fastdiv((uint32_t)a.OH);
+
+    const long long wgs = (ntiles + 3) / 4;
+    sh.xcd_chunk = (int)((wgs + 7) / 8);
+    hipLaunchKernelGGL((bd_conv_lane<KW, KA, P, ST>), dim3((unsigned)(sh.xcd_chunk * 8)), dim3(256), 0, a.stream,
+                       a.act, a.wgt, a.scale, a.offset, a.acc, a.out, sh);
+    return hip_ok(hipGetLastError());
+}
+
+// sel: 0 = large runs, 1 = small runs
+template <int KW, int KA>
+static int launch_lane_pair_impl(const ConvArgs &a, int sel)
+{
+    if (a.stride == 1) {
+        if (sel == 0) return launch_lane_cfg<KW, KA, LaneRun<KW, KA, 1>::BIG, 1>(a);
+        return launch_lane_cfg<KW, KA, LaneRun<KW, KA, 1>::SMALL, 1>(a);
+    }
+    if (a.stride == 2) {
+        if (sel == 0) return launch_lane_cfg<KW, KA, LaneRun<KW, KA, 2>::BIG, 2>(a);
+        return launch_lane_cfg<KW, KA, LaneRun<KW, KA, 2>::SMALL, 2>(a);
+    }
+    return EBS_ERR_UNSUPPORTED;
+}
+
+template <int KW, int KA> int launch_lane_pair(const ConvArgs &a, int sel);
+
+#define EBS_DEFINE_LANE_PAIR(KWV, KAV)                                                     \
+    template <> int launch_lane_pair<KWV, KAV>(const ConvArgs &a, int sel)                 \
+    {                                                                                      \
+        return launch_lane_pair_impl<KWV, KAV>(a, sel);                                    \
+    }
+
+}  // namespace ebs

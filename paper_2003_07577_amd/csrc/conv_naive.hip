@@ -11,6 +11,7 @@ namespace ebs {
 struct NaiveGeom {
     int H, W, K, R, S, stride, pad, OH, OW, cw;
     int wtop;      // 0: unsigned weight levels; else 2^k_w - 1 (signed weights 2q - wtop)
+    long long total_pos;   // N*(H+2)*(W+2): bordered positions of the packed input [word][position][plane]
 };
 
 template <int KW, int KA>
@@ -34,12 +35,12 @@ __device__ __forceinline__ int32_t naive_point(const uint32_t *__restrict__ act,
         for (int s = 0; s < g.S; ++s) {
             int wcol = ow * g.stride + s - g.pad + kActBorder;
             if (wcol < 0 || wcol >= Wp) continue;
-            const uint32_t *ap = act + (((n * Hp + hp) * Wp + wcol) * cw) * KA;
+            const long long apos = (n * Hp + hp) * Wp + wcol;
             const uint32_t *wp = wk + (long long)(r * g.S + s) * cw * kWgtGroup * KW;
             for (int word = 0; word < cw; ++word) {
                 uint32_t x[KA], q[KW];
 #pragma unroll
-                for (int j = 0; j < KA; ++j) x[j] = ap[word * KA + j];
+                for (int j = 0; j < KA; ++j) x[j] = act[(word * g.total_pos + apos) * KA + j];
 #pragma unroll
                 for (int i = 0; i < KW; ++i) q[i] = wp[(long long)word * kWgtGroup * KW + i];
 #pragma unroll
@@ -116,13 +117,15 @@ bd_requant_naive(const uint32_t *__restrict__ act, const uint32_t *__restrict__ 
         for (int j = 0; j < kMaxBits; ++j) planes[j] |= ((lv >> j) & 1u) << c;
     }
     const long long pos = (n * (g.OH + 2 * kActBorder) + oh + kActBorder) * (g.OW + 2 * kActBorder) + ow + kActBorder;
-    for (int j = 0; j < k_next; ++j) next[(pos * cwn + word) * k_next + j] = planes[j];
+    const long long total_next = (total / cwn) / ((long long)g.OH * g.OW) * (g.OH + 2 * kActBorder) * (g.OW + 2 * kActBorder);
+    for (int j = 0; j < k_next; ++j) next[(word * total_next + pos) * k_next + j] = planes[j];
 }
 
 template <int KW, int KA>
 static int launch(const ConvArgs &a)
 {
-    NaiveGeom g{a.H, a.W, a.K, a.R, a.S, a.stride, a.pad, a.OH, a.OW, a.cw, a.wtop};
+    NaiveGeom g{a.H, a.W, a.K, a.R, a.S, a.stride, a.pad, a.OH, a.OW, a.cw, a.wtop,
+                (long long)a.N * (a.H + 2 * kActBorder) * (a.W + 2 * kActBorder)};
     if (a.next) {
         long long total = (long long)a.N * a.OH * a.OW * ((a.K + 31) / 32);
         unsigned blocks = (unsigned)((total + 255) / 256);
@@ -154,32 +157,36 @@ static int dispatch(const ConvArgs &a)
 int launch_conv_naive(const ConvArgs &a) { return dispatch(a); }
 int launch_requant_naive(const ConvArgs &a) { return dispatch(a); }
 
-// Zero ring of a packed activation tensor [N][H+2][W+2][words_per_pos]: one thread per ring word.
+// Zero ring of a packed activation tensor [word][N][H+2][W+2][plane]: one thread per ring dword.
 __global__ void __launch_bounds__(256)
-zero_border_kernel(uint32_t *__restrict__ packed, int H, int W, int wpp, long long per_image, long long total)
+zero_border_kernel(uint32_t *__restrict__ packed, int H, int W, int planes, int wpp, long long per_image, long long total,
+                   long long total_pos)
 {
     long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= total) return;
     const int Hp = H + 2 * kActBorder, Wp = W + 2 * kActBorder;
     long long n = idx / per_image;
     long long rem = idx - n * per_image;
-    int word = (int)(rem % wpp);
+    int dword = (int)(rem % wpp);             // (word, plane) of the position
     int b = (int)(rem / wpp);                 // ring position: top row, bottom row, then left/right columns
     int hp, wp;
     if (b < Wp) { hp = 0; wp = b; }
     else if (b < 2 * Wp) { hp = Hp - 1; wp = b - Wp; }
     else { int c = b - 2 * Wp; hp = 1 + c / 2; wp = (c & 1) ? Wp - 1 : 0; }
-    packed[((n * Hp + hp) * Wp + wp) * wpp + word] = 0u;
+    const int word = dword / planes, j = dword - word * planes;
+    packed[(word * total_pos + (n * Hp + hp) * Wp + wp) * planes + j] = 0u;
 }
 
-int launch_zero_border(uint32_t *packed, int N, int H, int W, int wpp, hipStream_t st)
+int launch_zero_border(uint32_t *packed, int N, int H, int W, int words, int planes, hipStream_t st)
 {
     const int Wp = W + 2 * kActBorder;
+    const int wpp = words * planes;
     long long ring = 2LL * Wp + 2LL * H;
     long long per_image = ring * wpp;
     long long total = per_image * N;
     unsigned blocks = (unsigned)((total + 255) / 256);
-    hipLaunchKernelGGL(zero_border_kernel, dim3(blocks), dim3(256), 0, st, packed, H, W, wpp, per_image, total);
+    hipLaunchKernelGGL(zero_border_kernel, dim3(blocks), dim3(256), 0, st, packed, H, W, planes, wpp, per_image, total,
+                       (long long)N * (H + 2 * kActBorder) * Wp);
     return hip_ok(hipGetLastError());
 }
 

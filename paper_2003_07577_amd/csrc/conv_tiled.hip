@@ -24,9 +24,10 @@ static const char *const kNames[] = {
     "k4.tile16.ch2", "k4.tile16.ch1", "k4.tile16.ch4",
     "r4.tile64.ch4", "r4.tile32.ch4", "r4.tile16.ch4",
     "k4.wide.ch2", "k4.wide.ch1", "k4.wide.ch4",
+    "lane.big", "lane.small",
 };
 static constexpr int kNumVariants = sizeof(kNames) / sizeof(kNames[0]);
-enum { V_P4_64 = 0, V_P4_32 = 3, V_K4_64 = 6, V_K4_32 = 9, V_K4_16 = 12, V_R4_64 = 15, V_R4_32 = 16, V_R4_16 = 17, V_K4_WIDE = 18 };
+enum { V_P4_64 = 0, V_P4_32 = 3, V_K4_64 = 6, V_K4_32 = 9, V_K4_16 = 12, V_R4_64 = 15, V_R4_32 = 16, V_R4_16 = 17, V_K4_WIDE = 18, V_LANE = 21 };
 
 int conv_tiled_variant_count() { return kNumVariants; }
 const char *conv_tiled_variant_name(int v) { return (v >= 0 && v < kNumVariants) ? kNames[v] : "invalid"; }
@@ -47,9 +48,13 @@ static int run_fs(const ConvArgs &a, int v)
     return run_pair<FS>(a, v, 0);
 }
 
+int launch_conv_lane(const ConvArgs &a, int sel);
+int lane_run_length(int kw, int ka, int stride, int sel);
+
 static int run_variant(const ConvArgs &a, int v)
 {
     if (v < 0 || v >= kNumVariants) return EBS_ERR_UNSUPPORTED;
+    if (v >= V_LANE) return launch_conv_lane(a, v - V_LANE);
     if (a.R == 3 && a.S == 3) return run_fs<3>(a, v);     // unrolled 3x3 taps
     return run_fs<0>(a, v);
 }
@@ -119,8 +124,29 @@ int launch_conv_tiled(const ConvArgs &a, int variant)
     const long long positions = (long long)a.N * a.OH * a.OW;
     const int slot = ch_slot(a.cw);
     const int rs = a.R * a.S;
-    int order[7];
+    int order[9];
     int n = 0;
+    // Channel-per-lane kernel (3x3 filters): no LDS, scalar position arithmetic, direct 256-byte stores.  It wins
+    // where the per-work-group costs of the tiled kernel weigh most: few plane pairs (short kernels), and the
+    // 64-channel layers with their short reductions; not on the deepest layers (few positions: too few tiles), and
+    // not when many of a wave's 64 channel lanes would idle.  Measured on the ResNet-18 shapes, all 16 pairs.
+    if (rs == 9 && a.R == 3 && a.kw <= 4 && a.ka <= 4 && !a.wtop && positions >= 8192 && (a.cw & 1) == 0 &&
+        (a.K % 64 == 0 || a.K >= 256)) {
+        const int pairs = a.kw * a.ka;
+        if (pairs <= 4 || (a.cw == 2 && pairs <= 9 && !(a.ka == 4 && a.kw >= 3))) {
+            // small runs where the large ones leave fewer than six tiles per SIMD and divide the row
+            const int big = lane_run_length(a.kw, a.ka, a.stride, 0), small = lane_run_length(a.kw, a.ka, a.stride, 1);
+            int sel = 0;
+            if (big > 0 && small > 0 && a.OW >= big) {
+                const long long tiles_big = (long long)a.N * a.OH * ((a.OW + big - 1) / big) * ((a.K + 63) / 64);
+                if (tiles_big < 6 * 1024 && small < big && a.OW % small == 0) sel = 1;
+            } else {
+                sel = 1;
+            }
+            order[n++] = V_LANE + sel;
+            order[n++] = V_LANE + 1 - sel;
+        }
+    }
     // reduction split: 8 channels per wave for one-bit weights with 3-4 bit activations (4 would leave too
     // little arithmetic per step), else the 16-register tiles
     // (1x1 filters: only at one or two plane pairs; with more, the channel split is faster)
@@ -130,7 +156,10 @@ int launch_conv_tiled(const ConvArgs &a, int variant)
     // (32-channel pieces of each output row) up to 8 plane pairs; measured -15 % on 64->256 @56x56, -2..4 % on 256->64
     if (rs == 1 && a.cw <= 8 && a.kw * a.ka <= 8 && a.K >= 32) order[n++] = V_K4_WIDE + slot;
     // channel split: the 16-register tiles (interleaved sweeps: never slower than the 32-register ones)
-    if (a.K >= 4 * kt_of(16, a.kw, a.ka)) order[n++] = V_K4_16 + slot;
+    // (one-bit weights with 3-4 bit activations: little arithmetic per staged byte, so half-size chunks - twice
+    // the resident work-groups - are faster: 26 vs 45 us on 128->256 @28x28 stride 2 at (1,3))
+    const int kslot = (a.kw == 1 && a.ka >= 3 && a.cw % 4 == 0) ? 0 : slot;
+    if (a.K >= 4 * kt_of(16, a.kw, a.ka)) order[n++] = V_K4_16 + kslot;
     order[n++] = V_P4_32 + slot;
     order[n++] = V_P4_32 + 1;       // ch1: smallest staging footprint
     for (int i = 0; i < n; ++i) {

@@ -45,23 +45,16 @@
 #include "fastdiv.h"
 #include "requant.h"
 #include "tile_geometry.h"
-#include <cstdlib>
 
 namespace ebs {
 
 enum { MODE_P4 = 0, MODE_K4 = 1, MODE_R4 = 2, MODE_PL = 3 };
 
-// Experiment builds (-DEBS_EXPERIMENT) can switch phases of the kernel off through the
-// EBS_EXP_DBG environment variable to time them; production builds compile this away.
-#ifdef EBS_EXPERIMENT
-#define EBS_DBG(bit) (sh.dbg & (bit))
-#else
-#define EBS_DBG(bit) false
-#endif
-
 struct TiledShape {
     int K, R, S, stride, pad, OW, cw, Hp, Wp, RS;   // Hp, Wp: bordered grid
     int total;        // N*OH*OW output positions
+    int total_pos;    // N*Hp*Wp bordered input positions (packed input: [word][position][plane])
+    int total_next;   // REQ: N*OHn*OWn bordered positions of the next layer's packed tensor
     int nchunks;      // cw / CH reduction chunks staged one at a time
     int per_channel;
     int ucap;         // staged positions that fit the LDS allocation
@@ -77,7 +70,6 @@ struct TiledShape {
     int ring_total, ring_per_image;  // dwords of the zero ring of the next layer's packed tensor (all images / one)
     int wtop;         // 0: unsigned weight levels; else 2^k_w - 1 (signed weights 2q - wtop, Eq. 1a)
     int gather;       // 1x1 filter without padding: stage exactly the tile's own positions (no halo, no ring)
-    int dbg;          // experiment switches; only read in EBS_EXPERIMENT builds
 };
 
 template <int N> struct UVec;
@@ -144,9 +136,6 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
     using C = Cfg<KW, KA, PIX, KT, CH, MODE>;
     extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
     int32_t *otile = reinterpret_cast<int32_t *>(lds + sh.stage_dwords);
-#ifdef EBS_EXPERIMENT
-    const unsigned long long exp_t0 = wall_clock64();
-#endif
 
     // ---- which (position tile, channel block): dies take contiguous runs of logical blocks
     const int die = blockIdx.x & 7;
@@ -196,16 +185,20 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
     const int xtra_base = sh.ucap * CH * C::KAP;      // start of the fifth-plane region (five-bit activations)
     (void)xtra_base;
 
-    // ---- staging of one reduction chunk: positions [u_lo, u_hi] of the bordered
-    //      input are contiguous in memory; copy CH words (x KA planes) of each
-    const int n_stage = (gather ? t_last - t_first + 1 : u_hi - u_lo + 1) * CH;
+    // ---- staging of one reduction chunk: for every word, positions [u_lo, u_hi] of the bordered input
+    //      are contiguous in memory (packed input [word][position][plane]); the 256 threads split into
+    //      CH groups, one per word of the chunk, each copying its word's run with consecutive lanes on
+    //      consecutive positions (interleaving the words over the lanes instead was up to 30 % slower on
+    //      the deep stride-2 layers)
+    const int n_pos = gather ? t_last - t_first + 1 : u_hi - u_lo + 1;
+    constexpr int SG = 256 / CH;                 // threads per word
+    static_assert(256 % CH == 0, "chunk words must divide the work-group");
     auto stage = [&](int chunk) {
-        const unsigned src0 = ((unsigned)u_lo * sh.cw + chunk * CH) * KA;     // dword index, < 2^31
-        for (int x = tid; x < n_stage; x += 256) {
-            const int u = x / CH;
-            const int w = x - u * CH;
+        const int w = tid / SG;
+        const uint32_t *srcw = act + ((size_t)(chunk * CH + w) * (unsigned)sh.total_pos + (unsigned)u_lo) * KA;
+        for (int u = tid % SG; u < n_pos; u += SG) {
             const unsigned rel = gather ? (unsigned)(base_of(t_first + u) - u_lo) : (unsigned)u;
-            const uint32_t *src = act + (src0 + (rel * sh.cw + w) * KA);
+            const uint32_t *src = srcw + (size_t)rel * KA;
             uint32_t *dst = lds + (w * sh.ucap + u) * C::KAP;
             if constexpr (KA == 5) {
                 const UVec<4>::type v4 = {src[0], src[1], src[2], src[3]};
@@ -251,7 +244,6 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
         if (chunk > 0) __syncthreads();       // everyone is done with the previous chunk
         stage(chunk);
         __syncthreads();
-        if (EBS_DBG(2)) continue;
 
         // weight words of this tile: [k/16][tap][word][k%16][plane]; per 16-channel group a
         // wave-uniform base pointer, plus one running offset over (tap, word)
@@ -495,14 +487,14 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
                 const int row = wpx * C::TPW + p * 64 + lane;
                 if constexpr (BYTES) {
                     const int t = t_first + row;
-                    if (t < sh.total && !EBS_DBG(1)) {
+                    if (t < sh.total) {
                         const int n = (int)fd_div((uint32_t)t, sh.div_ohow);
                         const int rem = t - n * (int)sh.div_ohow.d;
                         const int oh = (int)fd_div((uint32_t)rem, sh.div_ow);
                         const int ow = rem - oh * sh.OW;
                         const size_t pos = ((size_t)n * sh.OHn + oh + kActBorder) * sh.OWn + ow + kActBorder;
                         const int byte = (kb0 >> 3) & 3;
-                        uint8_t *dstb = reinterpret_cast<uint8_t *>(packed_next + (pos * sh.cwn + (kb0 >> 5)) * kmax) + byte;
+                        uint8_t *dstb = reinterpret_cast<uint8_t *>(packed_next + ((size_t)(kb0 >> 5) * sh.total_next + pos) * kmax) + byte;
                         const int fill = kb0 + 8 >= sh.K ? 3 - byte : 0;     // the last channel block also clears the rest of its word
 #pragma unroll
                         for (int j = 0; j < kMaxBits; ++j) {
@@ -524,7 +516,6 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
                 }
             }
         }
-        if (EBS_DBG(1)) return;
         if constexpr (!BYTES) {
             __syncthreads();
             constexpr int WPB = C::KB / 32;                // packed words of a position this work-group owns
@@ -540,7 +531,7 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
                 const int oh = (int)fd_div((uint32_t)rem, sh.div_ow);
                 const int ow = rem - oh * sh.OW;
                 const size_t pos = ((size_t)n * sh.OHn + oh + kActBorder) * sh.OWn + ow + kActBorder;
-                uint32_t *dstw = packed_next + (pos * sh.cwn + word0 + wd) * kmax;
+                uint32_t *dstw = packed_next + ((size_t)(word0 + wd) * sh.total_next + pos) * kmax;
                 const uint8_t *src = pieces + row * C::REQ_ROWB + wd * 4;
                 for (int j = 0; j < kmax; ++j) dstw[j] = *reinterpret_cast<const uint32_t *>(src + j * C::REQ_NG);
             }
@@ -557,7 +548,8 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
             if (b < sh.OWn) { hp = 0; wp = b; }
             else if (b < 2 * sh.OWn) { hp = sh.OHn - 1; wp = b - sh.OWn; }
             else { const int cc = b - 2 * sh.OWn; hp = 1 + (cc >> 1); wp = (cc & 1) ? sh.OWn - 1 : 0; }
-            packed_next[(((size_t)n * sh.OHn + hp) * sh.OWn + wp) * wpp + word] = 0u;
+            const int wd = word / kmax, j = word - wd * kmax;
+            packed_next[((size_t)wd * sh.total_next + ((size_t)n * sh.OHn + hp) * sh.OWn + wp) * kmax + j] = 0u;
         }
         return;
     }
@@ -637,7 +629,6 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
                 }
             }
             __syncthreads();
-            if (EBS_DBG(1)) continue;
             // rows of this pass: row r of sub-tile w is position t_first + w*TPW + p*64 + r
             {
 #pragma unroll
@@ -649,7 +640,7 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
                     const size_t o = (size_t)t * sh.K + kq;
                     if (vec_ok) {
                         *reinterpret_cast<i32x4 *>(dst_acc + o) = v;
-                        if (!C::PLN && out_f32 && !EBS_DBG(8)) {
+                        if (!C::PLN && out_f32) {
                             f32x4 f = {fmaf((float)v[0], sc[0], of[0]), fmaf((float)v[1], sc[1], of[1]),
                                        fmaf((float)v[2], sc[2], of[2]), fmaf((float)v[3], sc[3], of[3])};
                             *reinterpret_cast<f32x4 *>(out_f32 + o) = f;
@@ -659,7 +650,7 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
                         for (int e = 0; e < 4; ++e) {
                             if (kq + e < sh.K) {
                                 dst_acc[o + e] = v[e];
-                                if (!C::PLN && out_f32 && !EBS_DBG(8)) out_f32[o + e] = fmaf((float)v[e], sc[e], of[e]);
+                                if (!C::PLN && out_f32) out_f32[o + e] = fmaf((float)v[e], sc[e], of[e]);
                             }
                         }
                     }
@@ -668,13 +659,6 @@ bd_conv_tiled(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt
             }
         }
     }
-#ifdef EBS_EXPERIMENT
-    if (EBS_DBG(8) && out_f32 && tid == 0) {
-        unsigned long long *tr = reinterpret_cast<unsigned long long *>(out_f32) + 2 * (size_t)logical;
-        tr[0] = exp_t0;
-        tr[1] = wall_clock64();
-    }
-#endif
 }
 
 // ------------------------------------------------------------------ launch
@@ -751,6 +735,7 @@ static int launch_cfg(const ConvArgs &a)
     sh.stride = a.stride; sh.pad = a.pad; sh.OW = a.OW; sh.cw = a.cw;
     sh.Hp = a.H + 2 * kActBorder; sh.Wp = a.W + 2 * kActBorder; sh.RS = a.R * a.S;
     sh.total = a.N * a.OH * a.OW;
+    sh.total_pos = a.N * sh.Hp * sh.Wp;
     sh.nchunks = a.cw / CH;
     sh.per_channel = a.per_channel;
     sh.wgroups = (a.K + kWgtGroup - 1) / kWgtGroup;
@@ -764,6 +749,7 @@ static int launch_cfg(const ConvArgs &a)
         sh.OHn = a.OH + 2 * kActBorder;
         sh.OWn = a.OW + 2 * kActBorder;
         sh.cwn = words_per_pixel(a.K);
+        sh.total_next = a.N * sh.OHn * sh.OWn;
         const long long ring_pos = 2LL * sh.OWn + 2LL * a.OH;          // ring positions of one image
         const long long per_image = ring_pos * sh.cwn * a.k_next;
         if (per_image * a.N > (1LL << 30)) return EBS_ERR_UNSUPPORTED;
@@ -783,9 +769,6 @@ static int launch_cfg(const ConvArgs &a)
     if (lds_bytes > kMaxLdsBytes || ucap > (1 << 28)) return EBS_ERR_UNSUPPORTED;
     sh.ucap = (int)ucap;
     sh.stage_dwords = (int)stage_dwords;
-#ifdef EBS_EXPERIMENT
-    if (const char *e = getenv("EBS_EXP_DBG")) sh.dbg = atoi(e);
-#endif
 
     long long ptiles = ((long long)sh.total + C::TP - 1) / C::TP;
     long long kblocks = ((long long)a.K + C::KB - 1) / C::KB;

@@ -18,7 +18,7 @@ constexpr int kMaxBits = 5;
 constexpr int kMaxCandidates = EBS_MAX_CANDIDATES;
 
 struct ConvArgs {
-    const uint32_t *act;   // packed activations  [N][H+2][W+2][cw][k_a], zero border of one position
+    const uint32_t *act;   // packed activations  [cw][N][H+2][W+2][k_a], zero border of one position
     const uint32_t *wgt;   // packed weights      [ceil(K/16)][R*S][cw][16][k_w]
     int N, C, H, W, K, R, S, stride, pad, OH, OW, cw, kw, ka;
     const float *scale;
@@ -28,7 +28,7 @@ struct ConvArgs {
     float *out;            // may be null
     hipStream_t stream;
     // fused re-quantisation (next != null): instead of acc/out the kernel writes the NEXT layer's
-    // packed activations [N][OH+2][OW+2][ceil(K/32)][k_next]; the zero ring is written first
+    // packed activations [ceil(K/32)][N][OH+2][OW+2][k_next]; the zero ring is written first
     uint32_t *next;
     float alpha;           // clip of the next layer's activation quantiser
     int k_next;            // its bitwidth
@@ -49,7 +49,7 @@ constexpr int kActTailDwords = 4;
 
 int launch_conv_naive(const ConvArgs &a);
 int launch_requant_naive(const ConvArgs &a);
-int launch_zero_border(uint32_t *packed, int N, int H, int W, int words_per_pos, hipStream_t st);
+int launch_zero_border(uint32_t *packed, int N, int H, int W, int words, int planes, hipStream_t st);
 // Returns EBS_ERR_UNSUPPORTED when the tiling cannot run this shape.
 int launch_conv_tiled(const ConvArgs &a, int variant);
 int launch_requant_tiled(const ConvArgs &a);

@@ -26,7 +26,7 @@ inline FastDiv make_fastdiv(uint32_t d)
     return f;
 }
 
-#if defined(__HIPCC__) || defined(__CUDACC__)
+#if defined(__HIPCC__)
 __device__ __forceinline__ uint32_t fd_div(uint32_t x, const FastDiv &f)
 {
     return (__umulhi(x, f.m) + (f.a ? x : 0u)) >> f.s;

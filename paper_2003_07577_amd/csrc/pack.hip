@@ -2,12 +2,15 @@
 // expansion w = sum_m c_m 2^m; Sec. 4.3, Eq. 12 and 15), channel bits packed
 // into 32-bit words.
 //
-// Activations: uint32 [n][h+1][w+1][word][plane] over a (H+2) x (W+2) grid per
+// Activations: uint32 [word][n][h+1][w+1][plane] over a (H+2) x (W+2) grid per
 // image whose outer ring of positions is all zero (activation level 0 is the
 // real value 0, so the ring is the convolution's zero padding); word = c / 32,
 // bit c % 32 of the word of plane j is digit j of channel c.  Channel bits
 // beyond C are zero.  Keeping the k_a planes of one word adjacent lets the
-// convolution fetch all planes of a reduction word with a single wide load.
+// convolution fetch all planes of a reduction word with a single wide load;
+// keeping the positions of one word adjacent makes the run of input positions
+// a filter row touches, for one reduction word, one contiguous piece of memory
+// (what a wave can fetch with scalar loads, and what a tile stages as a copy).
 //
 // Weights: uint32 [k / 16][tap = r*S+s][word][k % 16][plane]; output channels
 // beyond K (up to the next multiple of 16) are zero.  One reduction step of a
@@ -48,8 +51,9 @@ pack_act_generic(const uint8_t *__restrict__ levels, uint32_t *__restrict__ pack
             for (int j = 0; j < BITS; ++j) planes[j] |= ((lv >> j) & 1u) << c;
         }
     }
+    const long long total_pos = n_items / cw;
 #pragma unroll
-    for (int j = 0; j < BITS; ++j) packed[item * BITS + j] = planes[j];
+    for (int j = 0; j < BITS; ++j) packed[((long long)word * total_pos + pos) * BITS + j] = planes[j];
 }
 
 // ---- fast path for C % 32 == 0: 32 one-byte levels -> BITS plane words in registers.
@@ -121,7 +125,8 @@ pack_act_c32(const uint8_t *__restrict__ levels, uint32_t *__restrict__ packed,
         for (int j = 0; j < 4; ++j) plane[j] = low[j];
         if (BITS == 5) plane[4] = fifth_plane_of_32(d);
     }
-    uint32_t *dst = packed + ((size_t)n * items_per_image + item) * BITS;
+    const size_t pos_per_image = (size_t)(H + 2 * kActBorder) * Wp;
+    uint32_t *dst = packed + (((size_t)word * gridDim.y + n) * pos_per_image + pos) * BITS;
 #pragma unroll
     for (int j = 0; j < BITS; ++j) dst[j] = plane[j];
 }

@@ -17,6 +17,7 @@ namespace ebs {
 
 struct PlaneGeom {
     int H, W, K, R, S, stride, pad, OH, OW, cw;
+    long long total_pos;   // N*(H+2)*(W+2): bordered positions of the packed input [word][position][plane]
 };
 
 template <int KW, int KA>
@@ -48,14 +49,14 @@ bd_planes_naive(const uint32_t *__restrict__ act, const uint32_t *__restrict__ w
         for (int s = 0; s < g.S; ++s) {
             int wcol = ow * g.stride + s - g.pad + kActBorder;
             if (wcol < 0 || wcol >= Wp) continue;
-            const uint32_t *ap = act + (((n * Hp + hp) * Wp + wcol) * cw) * KA;
+            const long long apos = (n * Hp + hp) * Wp + wcol;
             const uint32_t *wp = wk + (long long)(r * g.S + s) * cw * kWgtGroup * KW;
             for (int word = 0; word < cw; ++word) {
 #pragma unroll
                 for (int i = 0; i < KW; ++i) {
                     const uint32_t q = wp[(long long)word * kWgtGroup * KW + i];
 #pragma unroll
-                    for (int j = 0; j < KA; ++j) p[i][j] += __builtin_popcount(q & ap[word * KA + j]);
+                    for (int j = 0; j < KA; ++j) p[i][j] += __builtin_popcount(q & act[(word * g.total_pos + apos) * KA + j]);
                 }
             }
         }
@@ -118,7 +119,8 @@ pow2_depthwise(const int32_t *__restrict__ planes, uint32_t plane_elems, FastDiv
 template <int KW, int KA>
 static int launch_planes(const ConvArgs &a)
 {
-    PlaneGeom g{a.H, a.W, a.K, a.R, a.S, a.stride, a.pad, a.OH, a.OW, a.cw};
+    PlaneGeom g{a.H, a.W, a.K, a.R, a.S, a.stride, a.pad, a.OH, a.OW, a.cw,
+                (long long)a.N * (a.H + 2 * kActBorder) * (a.W + 2 * kActBorder)};
     long long total = (long long)a.N * a.OH * a.OW * a.K;
     unsigned blocks = (unsigned)((total + 255) / 256);
     hipLaunchKernelGGL((bd_planes_naive<KW, KA>), dim3(blocks), dim3(256), 0, a.stream, a.act, a.wgt, g, a.acc, total);

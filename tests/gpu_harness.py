@@ -78,12 +78,12 @@ def assert_f32_close(out, ref, acc_ref, scale, per_channel):
 
 
 def unpack_activations(words, N, H, W, C, k_a):
-    """Test-side inverse of the activation packing: uint32 [n][H+2][W+2][word][plane]
+    """Test-side inverse of the activation packing: uint32 [word][n][H+2][W+2][plane]
     (one zero position all round every image, a few slack words at the very end)
     -> (levels NHWC, channel-padding bits, border words)."""
     cw = (C + 31) // 32
     Hp, Wp = H + 2, W + 2
-    w = np.asarray(words).view(np.uint32)[:N * Hp * Wp * cw * k_a].reshape(N, Hp, Wp, cw, k_a)
+    w = np.asarray(words).view(np.uint32)[:N * Hp * Wp * cw * k_a].reshape(cw, N, Hp, Wp, k_a).transpose(1, 2, 3, 0, 4)
     inner = w[:, 1:-1, 1:-1]
     border = np.concatenate([w[:, 0].reshape(-1), w[:, -1].reshape(-1), w[:, :, 0].reshape(-1), w[:, :, -1].reshape(-1)])
     bits = ((inner[..., None] >> np.arange(32, dtype=np.uint32)) & 1).astype(np.uint8)   # n,h,w,word,plane,bit
