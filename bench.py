@@ -55,18 +55,46 @@ def parse():
     return ap.parse_args()
 
 
-class CaseBuffers:
-    """Device-resident tensors of one case (torch owns memory only)."""
+ROTATE_BYTES = 256 << 20      # working set every timed loop cycles through (more than the last-level cache)
+MAX_SLOTS = 32
 
-    def __init__(self, case, inputs, shared, dev):
+
+class Pools:
+    """Flat device pools that the cases cut their rotating buffer sets from."""
+
+    def __init__(self, cases, dev):
+        import torch
+        import paper_2003_07577_amd as ebs
+        need_out = need_pa = 0
+        for c in cases:
+            L = c.layer
+            r = n_slots(c)
+            need_out = max(need_out, r * L.N * L.OH * L.OW * L.K)
+            need_pa = max(need_pa, r * (ebs.ebs_packed_activations_bytes(L.N, L.H, L.W, L.C, c.k_a) // 4 + 64))
+        self.acc = torch.empty(need_out, dtype=torch.int32, device=dev)
+        self.out = torch.empty(need_out, dtype=torch.float32, device=dev)
+        self.pa = torch.empty(need_pa, dtype=torch.int32, device=dev)
+
+
+def n_slots(case):
+    """Rotating buffer sets of a case: enough that input + output of consecutive launches cover ROTATE_BYTES."""
+    return max(2, min(MAX_SLOTS, -(-ROTATE_BYTES // conv_bytes(case))))
+
+
+class CaseBuffers:
+    """Device-resident tensors of one case (torch owns memory only).  Packed activations and the two
+    outputs exist n_slots() times, cut from shared pools; every pack / conv call moves on to the next
+    set, so that back-to-back launches neither re-read nor re-write lines that are still in a cache."""
+
+    def __init__(self, case, inputs, pools, dev):
         import torch
         import paper_2003_07577_amd as ebs
         L = case.layer
         self.case = case
         self.a = torch.from_numpy(inputs["a"]).to(dev)
         q = torch.from_numpy(inputs["q"]).to(dev)
-        self.pa = torch.empty(ebs.ebs_packed_activations_bytes(L.N, L.H, L.W, L.C, case.k_a) // 4,
-                              dtype=torch.int32, device=dev)
+        pa_words = ebs.ebs_packed_activations_bytes(L.N, L.H, L.W, L.C, case.k_a) // 4
+        pa_pitch = (pa_words + 63) // 64 * 64
         self.pw = torch.empty(ebs.ebs_packed_weights_bytes(L.K, L.C, L.R, L.S, case.k_w) // 4,
                               dtype=torch.int32, device=dev)
         ebs.ebs_pack_weights(q, L.K, L.C, L.R, L.S, case.k_w, self.pw)          # offline step
@@ -74,9 +102,21 @@ class CaseBuffers:
         self.offset = None if inputs["offset"] is None else torch.from_numpy(inputs["offset"]).to(dev)
         self.per_channel = inputs["per_channel"]
         n_out = L.N * L.OH * L.OW * L.K
-        # output buffers are rotated among a few allocations so that consecutive
-        # cases do not rewrite lines that are still in the last-level cache
-        self.acc, self.out = shared.outputs(n_out)
+        r = n_slots(case)
+        self.slots = [(pools.pa[i * pa_pitch:i * pa_pitch + pa_words], pools.acc[i * n_out:(i + 1) * n_out],
+                       pools.out[i * n_out:(i + 1) * n_out]) for i in range(r)]
+        self.i = 0
+        self.pa, self.acc, self.out = self.slots[0]
+
+    def next_slot(self):
+        self.i = (self.i + 1) % len(self.slots)
+        self.pa, self.acc, self.out = self.slots[self.i]
+
+    def pack_all(self, ebs, stream):
+        """Fills every slot's packed activations (the pools are shared between cases)."""
+        for _ in self.slots:
+            self.next_slot()
+            self.pack(ebs, stream)
 
     def pack(self, ebs, stream):
         L = self.case.layer
@@ -87,19 +127,6 @@ class CaseBuffers:
         ebs.ebs_mixed_conv2d_variant(variant, self.pa, self.pw, L.N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad,
                                      c.k_w, c.k_a, self.scale, self.offset, self.per_channel, self.acc, self.out,
                                      stream)
-
-
-class SharedOutputs:
-    def __init__(self, dev, max_elems, n_slots=4):
-        import torch
-        self.slots = [(torch.empty(max_elems, dtype=torch.int32, device=dev),
-                       torch.empty(max_elems, dtype=torch.float32, device=dev)) for _ in range(n_slots)]
-        self.i = 0
-
-    def outputs(self, n):
-        acc, out = self.slots[self.i % len(self.slots)]
-        self.i += 1
-        return acc[:n], out[:n]
 
 
 def conv_bytes(case):
@@ -130,17 +157,64 @@ def gpu_clocks():
     return out or None
 
 
+def source_digest():
+    """Digest of the HIP sources the library is built from: measured profiles are stamped with it."""
+    import glob
+    import hashlib
+    h = hashlib.sha256()
+    for path in sorted(glob.glob(os.path.join(ROOT, "paper_2003_07577_amd", "csrc", "*"))):
+        h.update(os.path.basename(path).encode())
+        h.update(open(path, "rb").read())
+    return h.hexdigest()[:16]
+
+
 def read_traffic(workload):
     """HBM bytes per convolution launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two
-    separate runs, scaled by a copy kernel of known size); the committed summary holds the figure."""
+    separate runs, scaled by a copy kernel of known size); the committed summary holds the figure
+    and the digest of the sources it was measured on.  Returns (bytes or None, note)."""
     path = os.path.join(ROOT, "profiles", f"bd_conv_{workload}_hbm_traffic.txt")
+    value = stamp = None
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch:"):
-                return float(line.split(":")[1].split()[0])
+                value = float(line.split(":")[1].split()[0])
+            if line.startswith("source_digest:"):
+                stamp = line.split(":")[1].split()[0]
     except OSError:
-        pass
-    return None
+        return None, "no committed traffic summary for this workload"
+    now = source_digest()
+    if stamp != now:
+        return None, f"committed traffic summary was measured on sources {stamp}, these are {now}: not used"
+    return value, f"profiles/bd_conv_{workload}_hbm_traffic.txt, sources {stamp}"
+
+
+def measured_peaks(ebs, torch, dev, stream):
+    """What the machine sustains for the two resources the kernels are bound by (library probes):
+    the AND + accumulating-bitcount pair on registers only, and a 256 MiB copy / fill."""
+    def timed(f, reps):
+        f()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(reps):
+            f()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / reps
+    blocks, trips = 256 * 8, 2000
+    seed = torch.randint(0, 2 ** 31 - 1, (512,), dtype=torch.int32, device=dev)
+    sink = torch.zeros(blocks * 256, dtype=torch.int32, device=dev)
+    t = min(timed(lambda: ebs.ebs_probe_and_bcnt(seed, sink, blocks, trips, stream), 5) for _ in range(3))
+    alu = ebs.ebs_probe_and_bcnt_pairs(blocks, trips) * 64 / t / 1e12
+    n = 256 << 20
+    src = torch.empty(n, dtype=torch.uint8, device=dev).random_(0, 255)
+    dst = torch.empty(n, dtype=torch.uint8, device=dev)
+    t_copy = min(timed(lambda: ebs.ebs_probe_copy(src, dst, n, 8192, stream), 5) for _ in range(3))
+    t_fill = min(timed(lambda: ebs.ebs_probe_copy(None, dst, n, 8192, stream), 5) for _ in range(3))
+    return {"alu_binary_tops": round(alu, 1), "hbm_copy_gbs": round(2 * n / t_copy / 1e9, 1),
+            "hbm_fill_gbs": round(n / t_fill / 1e9, 1),
+            "how": "ebs_probe_and_bcnt (register-only AND + accumulating bitcount, 2048 work-groups) and "
+                   "ebs_probe_copy on 256 MiB (copy counts read + written bytes; fill = write only)"}
 
 
 def cpu_baseline(cases):
@@ -206,11 +280,10 @@ def main():
         if not cases:
             print("--only matches no case", file=sys.stderr)
             sys.exit(1)
-    max_out = max(c.layer.N * c.layer.OH * c.layer.OW * c.layer.K for c in cases)
-    shared = SharedOutputs(dev, max_out)
+    pools = Pools(cases, dev)
     bufs = []
     for c in cases:
-        bufs.append(CaseBuffers(c, wl.make_inputs(c), shared, dev))
+        bufs.append(CaseBuffers(c, wl.make_inputs(c), pools, dev))
     torch.cuda.synchronize()
 
     if args.traffic_pass:
@@ -224,11 +297,12 @@ def main():
             b.pack(ebs, stream)
             b.conv(ebs, stream, args.variant)
             torch.cuda.synchronize()
-        print(json.dumps({"traffic_pass": True, "copy_bytes": n, "cases": len(bufs)}))
+        print(json.dumps({"traffic_pass": True, "copy_bytes": n, "cases": len(bufs), "source_digest": source_digest()}))
         return
 
     def step():
         for b in bufs:
+            b.next_slot()
             b.pack(ebs, stream)
             b.conv(ebs, stream, args.variant)
 
@@ -256,11 +330,13 @@ def main():
     for b in bufs:
         c = b.case
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        b.pack_all(ebs, stream)                  # the pools are shared: every slot gets this case's input
         for _ in range(10):
-            b.pack(ebs, stream)
+            b.next_slot()
             b.conv(ebs, stream, args.variant)
         ev[0].record(stream)
         for _ in range(args.kernel_reps):
+            b.next_slot()
             b.pack(ebs, stream)
         ev[1].record(stream)
         # the convolution launches in five batches: the mean over all of them is the figure used,
@@ -270,6 +346,7 @@ def main():
         marks = [torch.cuda.Event(enable_timing=True) for _ in range(nb)]
         for i in range(nb):
             for _ in range(per if i + 1 < nb else args.kernel_reps - per * (nb - 1)):
+                b.next_slot()
                 b.conv(ebs, stream, args.variant)
             marks[i].record(stream)
         ev[2] = marks[-1]
@@ -295,6 +372,8 @@ def main():
             "pack_hbm_gbs": round(pack_bytes(c) / pack_us / 1e3, 1),
             "binding_roof": "alu" if t_alu >= t_hbm else "hbm",
             "roof_us": round(max(t_alu, t_hbm), 2),
+            "frac_of_binding_roof": round(max(t_alu, t_hbm) / conv_us, 4),
+            "rotating_sets": len(b.slots),
         })
     achieved = conv_ops / conv_us_sum / 1e6
     roofline = {
@@ -303,8 +382,18 @@ def main():
         "frac": round(achieved / PEAK_BINARY_TOPS, 4), "traffic": None,
         "avg_launch_us": round(conv_us_sum / len(bufs), 2),
         "hbm_gbs_algorithmic": round(conv_bytes_sum / conv_us_sum / 1e3, 1),
-        "min_case_frac": min(r["alu_frac"] for r in table), "max_case_frac": max(r["alu_frac"] for r in table),
+        # per case, against the roof that binds it (ALU, or HBM at 8 TB/s where the 8 B per output take longer)
+        "min_case_frac": min(r["frac_of_binding_roof"] for r in table),
+        "max_case_frac": max(r["frac_of_binding_roof"] for r in table),
+        "min_case_alu_frac": min(r["alu_frac"] for r in table),
+        "cases_below_half": [f'{r["layer"]} ({r["k_w"]},{r["k_a"]}) {r["frac_of_binding_roof"]}' for r in table
+                             if r["frac_of_binding_roof"] < 0.5],
+        "timing": f"{args.kernel_reps} back-to-back launches per case after 10 warm-up launches, inputs and outputs "
+                  f"rotating over >= {ROTATE_BYTES >> 20} MiB",
     }
+    peaks = measured_peaks(ebs, torch, dev, stream)
+    roofline["measured_peak"] = peaks
+    roofline["frac_of_measured"] = round(achieved / peaks["alu_binary_tops"], 4)
     pack_roof = {
         "kernel": "pack_activations", "bound": "hbm", "achieved": round(pack_bytes_sum / pack_us_sum / 1e3, 1),
         "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(pack_bytes_sum / pack_us_sum / 1e3 / HBM_PEAK_GBS, 4),
@@ -521,9 +610,9 @@ def main():
             "resnet18": time_chain(wl.resnet18_chain(N=64), "configs[2] ResNet-18-shaped 3x3 stack (ImageNet sizes), bitwidths from {1..4}"),
         }
 
-    traffic = read_traffic(args.workload)
-    if traffic is not None:
-        roofline["traffic"] = traffic
+    traffic, note = read_traffic(args.workload)
+    roofline["traffic"] = traffic
+    roofline["traffic_source"] = note
 
     out = {
         "metric": "effective binary TOP/s and latency per mixed-precision conv layer; % of int roofline",

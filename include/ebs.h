@@ -46,7 +46,8 @@ typedef enum {
     EBS_ERR_NULL = -1,        /* a required pointer is NULL                         */
     EBS_ERR_BITWIDTH = -2,    /* k_w or k_a outside [1, 5]                          */
     EBS_ERR_SHAPE = -3,       /* non-positive extent, empty output, pad >= filter,
-                                 a tensor with 2^31 or more elements, or a reduction
+                                 a tensor with 2^31 or more elements, more than
+                                 2^31 - 1025 output positions, or a reduction
                                  whose largest sum C*R*S*(2^k_w-1)*(2^k_a-1) does
                                  not fit an int32                                   */
     EBS_ERR_ALIGN = -4,       /* a buffer is not 16-byte aligned                    */

@@ -29,14 +29,19 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "bd_oracle.c")
-_LIB = os.path.join(_HERE, "libbd_oracle.so")
+# EBS_ORACLE_SANITIZE=1 (set by tests/test_sanitizers.py for a child process that preloads the sanitizer
+# run-time) builds and loads the same source with AddressSanitizer and UndefinedBehaviorSanitizer.
+_SANITIZE = os.environ.get("EBS_ORACLE_SANITIZE") == "1"
+_LIB = os.path.join(_HERE, "libbd_oracle_san.so" if _SANITIZE else "libbd_oracle.so")
 _lib = None
 
 
 def build(force: bool = False) -> str:
     """Compile the C oracle with gcc (host only, OpenMP for the timed baseline)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c99", "-ffp-contract=off", "-Wall", "-Wextra",
+        opt = ["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+               "-fno-omit-frame-pointer"] if _SANITIZE else ["-O2"]
+        cmd = ["gcc", *opt, "-fopenmp", "-fPIC", "-shared", "-std=c99", "-ffp-contract=off", "-Wall", "-Wextra",
                "-o", _LIB, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB

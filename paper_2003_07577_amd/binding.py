@@ -10,7 +10,8 @@ import ctypes
 import os
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_PKG, "libebs.so")
+# EBS_LIBRARY_PATH: load another build of the same library (the host-sanitized one of the test suite)
+_LIB_PATH = os.environ.get("EBS_LIBRARY_PATH") or os.path.join(_PKG, "libebs.so")
 _lib = None
 
 _vp = ctypes.c_void_p

@@ -59,12 +59,31 @@ def _compile(src: str, objname: str, extra) -> str:
 def build_library(jobs: int = 8, extra=()) -> str:
     """Compile every .hip under csrc/ for gfx950 and link libebs.so."""
     os.makedirs(OBJDIR, exist_ok=True)
-    for old in glob.glob(os.path.join(OBJDIR, "*.o")):
+    for old in glob.glob(os.path.join(OBJDIR, "*.o")) + glob.glob(os.path.join(OBJDIR, "*.so")):
         os.remove(old)
     with concurrent.futures.ThreadPoolExecutor(max_workers=jobs) as ex:
         objs = list(ex.map(lambda j: _compile(j[0], j[1], j[2] + list(extra)), jobs_list()))
     subprocess.run([HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB, *objs], check=True)
     return LIB
+
+
+def build_host_sanitized() -> str:
+    """libebs_hostsan.so: the C-ABI argument layer (csrc/api.hip) with AddressSanitizer and
+    UndefinedBehaviorSanitizer on the HOST side only (device code is built as always), linked with the
+    objects of the regular build.  For the host-only tests; never run on a GPU under the sanitizer."""
+    if not glob.glob(os.path.join(OBJDIR, "*.o")):
+        build_library()
+    obj = os.path.join(OBJDIR, "api_hostsan.o")
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host",
+           "-fno-omit-frame-pointer", "-g", "-shared-libsan"]
+    subprocess.run([HIPCC, *FLAGS, *san, "-c", os.path.join(CSRC, "api.hip"), "-o", obj], check=True,
+                   stderr=subprocess.DEVNULL)
+    others = [o for o in sorted(glob.glob(os.path.join(OBJDIR, "*.o")))
+              if os.path.basename(o) not in ("api.o", "api_hostsan.o")]
+    lib = os.path.join(OBJDIR, "libebs_hostsan.so")
+    subprocess.run([HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", "-fsanitize=address", "-fsanitize=undefined",
+                    "-fno-gpu-sanitize", "-shared-libsan", "-o", lib, obj, *others], check=True)
+    return lib
 
 
 if __name__ == "__main__":

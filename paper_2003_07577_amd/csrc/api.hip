@@ -2,6 +2,9 @@
 // Everything behind these calls runs in the library's own HIP kernels.
 #include "ebs_internal.h"
 
+#include <cstring>
+#include <mutex>
+
 namespace ebs {
 int pack_activations(const uint8_t *levels, uint32_t *packed, int N, int H, int W, int C, int bits, hipStream_t st);
 int pack_weights(const uint8_t *levels, uint32_t *packed, int K, int C, int RS, int bits, hipStream_t st);
@@ -12,6 +15,29 @@ hipError_t &last_hip_error()
 {
     static thread_local hipError_t e = hipSuccess;
     return e;
+}
+
+const DeviceShape *device_shape()
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static DeviceShape shapes[kMaxDevices];
+    static bool known[kMaxDevices];
+    int dev = 0;
+    if (hip_ok(hipGetDevice(&dev))) return nullptr;
+    if (dev < 0 || dev >= kMaxDevices) {
+        last_hip_error() = hipErrorInvalidDevice;
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> lock(mu);
+    if (!known[dev]) {
+        hipDeviceProp_t prop;
+        if (hip_ok(hipGetDeviceProperties(&prop, dev))) return nullptr;
+        shapes[dev].cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 1;
+        shapes[dev].gfx950 = std::strncmp(prop.gcnArchName, "gfx950", 6) == 0;
+        known[dev] = true;
+    }
+    return &shapes[dev];
 }
 
 static const long long kMaxElems = (1LL << 31) - 1;
@@ -53,6 +79,9 @@ static int check_conv(ConvArgs &a, const void *p0, const void *p1, bool need_sca
     a.OW = (a.W + 2 * a.pad - a.S) / a.stride + 1;
     a.cw = words_per_pixel(a.C);
     if ((long long)a.N * a.OH * a.OW * a.K > kMaxElems) return EBS_ERR_SHAPE;
+    // kernels number output positions in 32 bits and round the last tile up (tiles of at most 1024 positions);
+    // check_act_shape already keeps N*(H+2)*(W+2) below 2^29, so this is a second fence, not the first
+    if ((long long)a.N * a.OH * a.OW > kMaxElems - 1024) return EBS_ERR_SHAPE;
     // the largest accumulator, C*R*S*(2^k_w - 1)*(2^k_a - 1), must fit an int32
     if ((long long)a.C * a.R * a.S * ((1 << a.kw) - 1) * ((1 << a.ka) - 1) > kMaxElems) return EBS_ERR_SHAPE;
     if (!aligned16(p0) || !aligned16(p1) || !aligned16(a.acc) || (a.out && !aligned16(a.out)) || !aligned16(a.next))

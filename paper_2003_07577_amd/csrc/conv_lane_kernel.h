@@ -212,6 +212,9 @@ static int launch_lane_cfg(const ConvArgs &a)
     sh.div_runs = make_fastdiv((uint32_t)sh.runs);
     sh.div_oh = make_fastdiv((uint32_t)a.OH);
 
+    const DeviceShape *dev = device_shape();
+    if (!dev) return EBS_ERR_HIP;
+    if (!dev->gfx950) return EBS_ERR_UNSUPPORTED;       // run lengths and die numbering are gfx950's
     const long long wgs = (ntiles + 3) / 4;
     sh.xcd_chunk = (int)((wgs + 7) / 8);
     hipLaunchKernelGGL((bd_conv_lane<KW, KA, P, ST>), dim3((unsigned)(sh.xcd_chunk * 8)), dim3(256), 0, a.stream,

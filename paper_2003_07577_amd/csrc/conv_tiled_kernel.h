@@ -718,7 +718,6 @@ template <int KW, int KA> struct TileSel<4, KW, KA> {
 
 static constexpr size_t kMaxLdsBytes = 64 * 1024;       // per work-group (dynamic LDS without opt-in)
 static constexpr size_t kLdsPerCu = 160 * 1024;         // gfx950
-static constexpr int kNumCus = 256;
 
 template <int KW, int KA, int BUDGET, int CH, int MODE, int FS, bool REQ = false, bool SGN = false>
 static int launch_cfg(const ConvArgs &a)
@@ -781,7 +780,10 @@ static int launch_cfg(const ConvArgs &a)
 
     // A grid that fits the machine in one go is dealt unevenly to the compute units; asking
     // for more LDS than needed caps the work-groups per unit at ceil(nblocks / units).
-    long long per_cu = (nblocks + kNumCus - 1) / kNumCus;
+    const DeviceShape *dev = device_shape();
+    if (!dev) return EBS_ERR_HIP;
+    if (!dev->gfx950) return EBS_ERR_UNSUPPORTED;       // tile sizes, LDS budget and die numbering are gfx950's
+    long long per_cu = (nblocks + dev->cus - 1) / dev->cus;
     if (per_cu >= 2 && per_cu < 8) {
         size_t want = kLdsPerCu / (size_t)(per_cu + 1) + 512;
         if (want > kMaxLdsBytes) want = kMaxLdsBytes;

@@ -70,6 +70,14 @@ int aggregate_activations(const float *x, size_t count, float alpha, const int *
 int conv_tiled_variant_count();
 const char *conv_tiled_variant_name(int variant);
 
+// What the launch heuristics assume of the current device, read from the runtime once per device.
+// nullptr: the runtime gave no device (the error is in last_hip_error()).
+struct DeviceShape {
+    int cus;            // compute units
+    bool gfx950;        // the architecture these kernels are written and tuned for
+};
+const DeviceShape *device_shape();
+
 // Last HIP error this thread's library calls have seen (hipSuccess if none).
 hipError_t &last_hip_error();
 inline int hip_ok(hipError_t e)

@@ -6,6 +6,16 @@
 
 namespace ebs {
 
+// acc + bitcount(x) in one instruction (v_bcnt_u32_b32 adds its second operand), written out as in the
+// convolution kernels: left to itself the optimiser regroups sums of bitcounts into count + three-operand add,
+// 2.5 issue slots per pair instead of 2, and the probe would under-measure the peak it is there to establish.
+__device__ __forceinline__ uint32_t probe_bcnt_acc(uint32_t x, uint32_t acc)
+{
+    uint32_t d;
+    asm("v_bcnt_u32_b32 %0, %1, %2" : "=v"(d) : "v"(x), "v"(acc));
+    return d;
+}
+
 // Each lane keeps 32 accumulators and applies, per loop trip, 8 scalar operands
 // to 4 vector operands: 32 (v_and_b32, v_bcnt_u32_b32) pairs, no memory traffic.
 __global__ void __launch_bounds__(256)
@@ -28,7 +38,7 @@ probe_and_bcnt_kernel(const uint32_t *__restrict__ seed, uint32_t *__restrict__ 
 #pragma unroll
             for (int p = 0; p < 4; ++p)
 #pragma unroll
-                for (int c = 0; c < 8; ++c) acc[p][c] += __builtin_popcount(q[c] & x[p]);
+                for (int c = 0; c < 8; ++c) acc[p][c] = probe_bcnt_acc(q[c] & x[p], acc[p][c]);
 #pragma unroll
             for (int p = 0; p < 4; ++p) x[p] = __builtin_amdgcn_mov_dpp(x[p], 0x130 /* wave_shl:1 */, 0xf, 0xf, false);
         }

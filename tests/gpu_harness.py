@@ -13,6 +13,28 @@ def _dev():
     return torch.device("cuda:0")
 
 
+# Shapes of the every-variant parity sweep and, per shape, tilings that must accept it (for every bit pair up
+# to five bits); the host test checks the acceptance without a GPU, the GPU test that they ran.
+VARIANT_GEOS = [  # N, C, H, W, K, R, S, stride, pad
+    (2, 64, 20, 20, 40, 3, 3, 1, 1),      # several pixel tiles, K ragged vs 16
+    (3, 100, 9, 11, 17, 3, 3, 2, 1),      # C ragged vs 32, stride 2, odd sizes
+    (1, 16, 13, 7, 5, 1, 1, 1, 0),        # 1x1, half-filled word
+    (2, 33, 8, 8, 3, 5, 5, 1, 2),         # 5x5 filter, pad 2
+    (1, 256, 7, 7, 70, 3, 3, 1, 1),       # deep reduction
+    (2, 40, 10, 9, 33, 3, 2, 3, 0),       # asymmetric filter, stride 3, no pad
+]
+MUST_ACCEPT = [
+    {"p4.tile32.ch2", "k4.tile16.ch2", "k4.tile16.ch1", "k4.tile32.ch2"},
+    {"p4.tile32.ch4", "k4.tile16.ch4", "k4.tile16.ch2", "r4.tile16.ch4"},
+    {"p4.tile32.ch1", "k4.tile16.ch1", "k4.tile32.ch1"},
+    set(),                                 # pad 2 exceeds the stored zero ring: the per-output kernel only
+    {"r4.tile16.ch4", "k4.tile16.ch4", "p4.tile32.ch4"},
+    {"p4.tile32.ch2", "k4.tile16.ch2"},
+]
+# the channel-per-lane kernel (3x3 filters, bitwidths up to four): shapes whose rows hold a short run
+MUST_ACCEPT_LANE = [{"lane.small"}, {"lane.small"}, set(), set(), {"lane.small"}, set()]
+
+
 def geometry(inp, stride, pad):
     N, H, W, C = inp["a"].shape
     K, R, S, _ = inp["q"].shape
@@ -57,12 +79,21 @@ def conv(d, variant=0, stream=None, want_f32=True):
 
 
 def run_case(inp, k_w, k_a, stride, pad, variant=0):
-    """Full hot path on the GPU; returns (acc int32 NHWC, out float32 NHWC, device dict)."""
+    """Full hot path on the GPU; returns (acc int32 NHWC, out float32 NHWC, device dict).
+    The convolution is launched twice into re-poisoned outputs and the two results must be
+    byte-identical: integer accumulation has one right answer, so any run-to-run difference is a race."""
     import torch
     d = upload(inp, k_w, k_a, stride, pad)
     pack(d)
     conv(d, variant)
     torch.cuda.synchronize()
+    first_acc, first_out = d["acc"].clone(), d["out"].clone()
+    d["acc"].fill_(POISON)
+    d["out"].fill_(float("nan"))
+    conv(d, variant)
+    torch.cuda.synchronize()
+    assert torch.equal(first_acc, d["acc"]), "two launches of the same case differ (int32)"
+    assert torch.equal(first_out.view(torch.int32), d["out"].view(torch.int32)), "two launches of the same case differ (fp32)"
     return d["acc"].cpu().numpy(), d["out"].cpu().numpy(), d
 
 

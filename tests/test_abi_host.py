@@ -107,6 +107,44 @@ def test_conv_argument_errors(lib):
     assert ei.value.status == -1
 
 
+def test_position_count_stays_far_below_32_bits(lib):
+    """Kernels number output positions in 32 bits and round the last tile up: the interface must refuse shapes
+    whose bordered input has 2^29 positions or more (its packed form would pass 2^31 bytes per plane and word),
+    which keeps N*OH*OW, at most N*H*W for every filter, far from the 32-bit limit."""
+    for (N, H, W) in [(1 << 19, 32, 32), (1, 1 << 15, 1 << 15), (1 << 29, 1, 1)]:
+        assert ebs.ebs_packed_activations_bytes(N, H, W, 1, 1) == 0, (N, H, W)
+        assert _conv(N=N, H=H, W=W, C=1, K=1, R=1, S=1, pad=0, k_w=1, k_a=1) == -3, (N, H, W)
+    # the largest accepted square image of one channel: its position count is below 2^29
+    assert ebs.ebs_packed_activations_bytes(1, 23000, 23000, 1, 1) > 0
+    assert 23002 * 23002 < 1 << 29
+
+
+def test_tilings_accept_the_parity_shapes(lib):
+    """Which tilings take which shape is host logic: every tiling in the must-accept sets of the every-variant
+    parity sweep has to get past the host checks for every bit pair (it then tries to launch, which fails here
+    for want of a device; EBS_ERR_UNSUPPORTED, -5, is the answer that must not come)."""
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("host-only probe with fake pointers: not on a machine with a GPU")
+    import sys
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from gpu_harness import MUST_ACCEPT, MUST_ACCEPT_LANE, VARIANT_GEOS
+    names = {ebs.ebs_conv_variant_name(v): v for v in range(ebs.ebs_conv_variant_count() + 1)}
+    for gi, (N, C, H, W, K, R, S, st, pad) in enumerate(VARIANT_GEOS):
+        for kw in range(1, 6):
+            for ka in range(1, 6):
+                need = set(MUST_ACCEPT[gi]) | (MUST_ACCEPT_LANE[gi] if kw <= 4 and ka <= 4 else set())
+                for name in sorted(need):
+                    rc = ebs.ebs_mixed_conv2d_variant(names[name], FAKE, FAKE, N, C, H, W, K, R, S, st, pad, kw, ka,
+                                                      FAKE, None, 0, FAKE, FAKE, None, check=False)
+                    assert rc != -5, (gi, kw, ka, name)
+                # and a tiling that cannot take the shape says so instead of launching
+                if pad > 1:
+                    for v in range(2, ebs.ebs_conv_variant_count() + 1):
+                        assert ebs.ebs_mixed_conv2d_variant(v, FAKE, FAKE, N, C, H, W, K, R, S, st, pad, kw, ka, FAKE,
+                                                            None, 0, FAKE, FAKE, None, check=False) == -5
+
+
 def test_pack_argument_errors(lib):
     assert ebs.ebs_pack_weights(None, 16, 16, 3, 3, 2, FAKE, check=False) == -1
     assert ebs.ebs_pack_weights(FAKE, 16, 16, 3, 3, 2, None, check=False) == -1

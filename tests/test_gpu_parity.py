@@ -6,8 +6,8 @@ import pytest
 
 import ebs_workloads as wl
 import paper_2003_07577_amd as ebs
-from gpu_harness import (POISON, assert_f32_close, conv, pack, run_case, unpack_activations, unpack_weights,
-                         upload)
+from gpu_harness import (MUST_ACCEPT, MUST_ACCEPT_LANE, POISON, VARIANT_GEOS, assert_f32_close, conv, pack, run_case,
+                         unpack_activations, unpack_weights, upload)
 
 pytestmark = pytest.mark.gpu
 
@@ -98,39 +98,43 @@ def test_check_levels_flag():
 
 
 # ------------------------------------------------------------------ all bit pairs, several tiles, ragged tails
-GEOS = [  # N, C, H, W, K, R, S, stride, pad
-    (2, 64, 20, 20, 40, 3, 3, 1, 1),      # several pixel tiles, K ragged vs 16
-    (3, 100, 9, 11, 17, 3, 3, 2, 1),      # C ragged vs 32, stride 2, odd sizes
-    (1, 16, 13, 7, 5, 1, 1, 1, 0),        # 1x1, half-filled word
-    (2, 33, 8, 8, 3, 5, 5, 1, 2),         # 5x5 filter, pad 2
-    (1, 256, 7, 7, 70, 3, 3, 1, 1),       # deep reduction
-    (2, 40, 10, 9, 33, 3, 2, 3, 0),       # asymmetric filter, stride 3, no pad
-]
+GEOS = VARIANT_GEOS
 
 
 @pytest.mark.parametrize("kw,ka", BITS)
 def test_all_bit_pairs_every_variant(oracle_mod, kw, ka):
+    import torch
     for gi, (N, C, H, W, K, R, S, st, pad) in enumerate(GEOS):
         inp = wl.random_case(9000 + 100 * gi + 4 * kw + ka, N, C, H, W, K, R, S, st, pad, kw, ka,
                              per_channel=(gi % 2 == 1), with_offset=(gi % 3 == 0))
         ref = oracle_mod.conv2d_levels(inp["a"], inp["q"], st, pad)
         fref = oracle_mod.dequant(ref, inp["scale"], inp["offset"], inp["per_channel"])
+        ran = set()
         for v in _variants():
-            import torch
             d = upload(inp, kw, ka, st, pad)
             pack(d)
             g = d["g"]
-            rc = ebs.ebs_mixed_conv2d_variant(v, d["pa"], d["pw"], g["N"], g["C"], g["H"], g["W"], g["K"],
-                                              g["R"], g["S"], st, pad, kw, ka, d["scale"], d["offset"],
-                                              d["per_channel"], d["acc"], d["out"], None, check=False)
+            launch = lambda: ebs.ebs_mixed_conv2d_variant(v, d["pa"], d["pw"], g["N"], g["C"], g["H"], g["W"], g["K"],
+                                                          g["R"], g["S"], st, pad, kw, ka, d["scale"], d["offset"],
+                                                          d["per_channel"], d["acc"], d["out"], None, check=False)
+            rc = launch()
             torch.cuda.synchronize()
             print(f"[case] geo{gi} kw={kw} ka={ka} variant={v}:{ebs.ebs_conv_variant_name(v)} rc={rc}", flush=True)
             if rc == -5 and v >= 2:
-                continue          # this tiling does not take this shape; the heuristic never picks it
+                continue          # this tiling does not take this shape (the must-accept sets are checked below)
             assert rc == 0
+            ran.add(ebs.ebs_conv_variant_name(v))
             acc = d["acc"].cpu().numpy()
             assert np.array_equal(acc, ref), (gi, kw, ka, v, int((acc != ref).sum()))
             assert_f32_close(d["out"].cpu().numpy(), fref, ref, inp["scale"], inp["per_channel"])
+            # race check: a second launch into re-poisoned outputs must give the same bytes
+            first = d["acc"].clone()
+            d["acc"].fill_(POISON)
+            assert launch() == 0
+            torch.cuda.synchronize()
+            assert torch.equal(first, d["acc"]), (gi, kw, ka, v, "two launches differ")
+        need = set(MUST_ACCEPT[gi]) | (MUST_ACCEPT_LANE[gi] if kw <= 4 and ka <= 4 else set())
+        assert need <= ran, f"geo{gi} ({kw},{ka}): tilings that must take this shape did not run: {sorted(need - ran)}"
 
 
 # ------------------------------------------------------------------ edge cases
@@ -234,7 +238,7 @@ def test_mfma_i8_comparison_matches_oracle(oracle_mod):
     # unsupported channel count is an error code, not a crash
     rc = ebs.ebs_mixed_conv2d_mfma_i8(a, q, 1, 16, 4, 4, 8, 3, 3, 1, 1, sc, None, 0, acc, out, None, check=False)
     assert rc == -5
-    # full-size deep layers (few output positions: the reduction is split among work-groups), with and without fp32
+    # full-size deep layers (few output positions, long reductions), with and without fp32
     for c in wl.config_cases(3):
         if (c.k_w, c.k_a) != (4, 4) or c.layer_index not in (3, 6):
             continue

@@ -67,6 +67,36 @@ def test_weight_levels_match_oracle(oracle_mod, bits):
             assert diff.mean() < 1e-4
 
 
+def test_activation_levels_against_float64_definition(oracle_mod):
+    """ebs_quantize_activations against Eq. 1b-1c in float64, directly: a level may differ only where
+    (2^b - 1) clip(x, 0, alpha) / alpha + 1/2 is within single-precision rounding distance of an integer."""
+    import torch
+    rng = np.random.default_rng(4242)
+    total = differing = 0
+    for bits in (1, 2, 3, 4, 5, 8):
+        for alpha in (6.0, 2.37, 0.5):
+            x = np.concatenate([rng.normal(0, alpha, 50000), rng.uniform(-1, alpha + 1, 50000),
+                                alpha * (np.arange(0, 2 ** bits) + 0.5) / (2 ** bits - 1)]).astype(np.float32)
+            print(f"[case] quantize_activations-vs-f64 bits={bits} alpha={alpha}", flush=True)
+            dx = torch.from_numpy(x).to(_dev())
+            lv = torch.full((x.size,), 255, dtype=torch.uint8, device=_dev())
+            ebs.ebs_quantize_activations(dx, x.size, alpha, bits, lv)
+            torch.cuda.synchronize()
+            got = lv.cpu().numpy().astype(np.int64)
+            n = (1 << bits) - 1
+            a32 = float(np.float32(alpha))
+            y = n * np.clip(x.astype(np.float64), 0.0, a32) / a32 + 0.5
+            ref = np.floor(y).astype(np.int64)
+            window = 2.0 ** -22 * (2 * np.abs(y) + 1.0)
+            diff = got != ref
+            assert np.all(np.abs(y[diff] - np.round(y[diff])) < window[diff])
+            assert np.all(np.abs(got - ref)[diff] == 1)
+            total += x.size
+            differing += int(diff.sum())
+    print(f"[info] {differing} of {total} activation levels differ from the float64 decision (exact ties included)", flush=True)
+    assert differing <= 2e-3 * total
+
+
 def test_weight_levels_degenerate_inputs(oracle_mod):
     import torch
     for w in (np.zeros(300, np.float32), np.full(70, -2.5, np.float32), np.array([1e-30, -1e-30, 0], np.float32),

@@ -64,6 +64,48 @@ def test_requant_levels_match_oracle(oracle_mod, kw, ka):
             _check(oracle_mod, inp, kw, ka, st, pad, alpha, k_next, f"geo{gi}")
 
 
+def _f64_levels_and_window(acc, scale, offset, per_channel, alpha, bits):
+    """Eq. 1b-1c in float64 on x = scale*acc + offset (scale, offset as the float32 values given), and the
+    distance from a rounding boundary within which a single-precision evaluation may decide otherwise."""
+    sc = np.asarray(scale, np.float64).reshape(-1)
+    of = np.zeros_like(sc) if offset is None else np.asarray(offset, np.float64).reshape(-1)
+    if not per_channel:
+        sc, of = sc[:1], of[:1]
+    n = (1 << bits) - 1
+    x = sc * acc.astype(np.float64) + of
+    y = n * np.clip(x, 0.0, alpha) / alpha + 0.5
+    qs = n / alpha
+    window = 2.0 ** -22 * (qs * (np.abs(sc * acc) + np.abs(of)) + np.abs(y) + 1.0)
+    return np.floor(y).astype(np.int64), y, window
+
+
+def test_requant_levels_against_float64_definition(oracle_mod):
+    """The fused call's levels against Eq. 1b-1c evaluated in float64, directly (not through the
+    single-precision oracle): equal everywhere except where (2^b - 1) x / alpha + 1/2 lies within
+    single-precision rounding distance of an integer; such positions are counted and must be rare."""
+    total = differing = 0
+    for gi, (N, C, H, W, K, R, S, st, pad) in enumerate(GEOS[:6]):
+        for (kw, ka) in [(1, 1), (2, 3), (4, 4)]:
+            inp = wl.random_case(7700 + 10 * gi + kw * 4 + ka, N, C, H, W, K, R, S, st, pad, kw, ka,
+                                 per_channel=(gi % 2 == 0), with_offset=True)
+            top = C * R * S * (2 ** kw - 1) * (2 ** ka - 1)
+            inp["scale"] = (inp["scale"] * np.float32(60.0 / top)).astype(np.float32)
+            inp["offset"] = (inp["offset"] * np.float32(10.0) - np.float32(0.5)).astype(np.float32)
+            alpha, k_next = 6.0, 1 + (gi + kw) % 5
+            print(f"[case] requant-vs-f64 geo{gi} kw={kw} ka={ka} k_next={k_next}", flush=True)
+            nxt, g = _requant_gpu(inp, kw, ka, st, pad, alpha, k_next)
+            acc = oracle_mod.conv2d_levels(inp["a"], inp["q"], st, pad)
+            lv, _, _ = unpack_activations(nxt.cpu().numpy(), g["N"], g["OH"], g["OW"], g["K"], k_next)
+            ref, y, window = _f64_levels_and_window(acc, inp["scale"], inp["offset"], inp["per_channel"], alpha, k_next)
+            diff = lv.astype(np.int64) != ref
+            assert np.all(np.abs(y[diff] - np.round(y[diff])) < window[diff]), "a level differs away from a rounding boundary"
+            assert np.all(np.abs(lv.astype(np.int64) - ref)[diff] == 1)
+            total += ref.size
+            differing += int(diff.sum())
+    print(f"[info] {differing} of {total} levels differ from the float64 decision, all inside the rounding window", flush=True)
+    assert differing <= 1e-4 * total
+
+
 def test_requant_saturation_and_relu(oracle_mod):
     """All outputs above alpha -> top level everywhere; all below zero -> level 0 everywhere."""
     inp = wl.random_case(1, 1, 64, 6, 6, 32, 3, 3, 1, 1, 2, 2)

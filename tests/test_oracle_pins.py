@@ -314,8 +314,14 @@ def test_requant_per_channel_and_general_inputs_close_to_float64(oracle_mod):
     y = 7 * np.clip(x, 0, alpha) / alpha + 0.5
     ref = np.floor(y).astype(np.int64)
     diff = got != ref
-    assert np.all(np.abs(y[diff] - np.round(y[diff])) < 1e-4)          # only at rounding boundaries
-    assert diff.mean() < 0.01
+    # what single precision can do: x carries one rounding of an FMA whose terms are |scale*acc| and |offset|,
+    # qs one rounding, the last FMA one more - a few units of 2^-24 of those magnitudes.  A level may differ
+    # from the float64 decision only if y lies that close to an integer.
+    qs = 7.0 / alpha
+    window = 2.0 ** -22 * (qs * (np.abs(sc.astype(np.float64) * acc) + np.abs(of.astype(np.float64))) + np.abs(y) + 1.0)
+    assert window.max() < 3e-5
+    assert np.all(np.abs(y[diff] - np.round(y[diff])) < window[diff])  # only at rounding boundaries
+    assert diff.mean() < 1e-3
     # per-layer call equals per-channel call with constant arrays
     a = oracle_mod.requant_levels(acc, np.float32(0.004), np.float32(0.1), False, alpha, bits)
     b = oracle_mod.requant_levels(acc, np.full(K, 0.004, np.float32), np.full(K, 0.1, np.float32), True, alpha, bits)
