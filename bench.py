@@ -50,6 +50,8 @@ def parse():
     ap.add_argument("--traffic-pass", action="store_true",
                     help="no timing: one copy of known size (256 MiB) and one pass of the workload, to be run under "
                          "`rocprofv3 --pmc FETCH_SIZE` and again under `--pmc WRITE_SIZE`")
+    ap.add_argument("--traffic-reps", type=int, default=1,
+                    help="with --traffic-pass: passes of the workload (rotating buffers); the last one is warm")
     ap.add_argument("--cases-out", default=None, help="write the per-case table (JSON) here")
     ap.add_argument("--variant", type=int, default=0, help="conv kernel variant (0 = library heuristic)")
     return ap.parse_args()
@@ -293,11 +295,13 @@ def main():
         torch.cuda.synchronize()
         ebs.ebs_probe_copy(src, dst, n, 4096, stream)
         torch.cuda.synchronize()
-        for b in bufs:
-            b.pack(ebs, stream)
-            b.conv(ebs, stream, args.variant)
-            torch.cuda.synchronize()
-        print(json.dumps({"traffic_pass": True, "copy_bytes": n, "cases": len(bufs), "source_digest": source_digest()}))
+        for _ in range(max(1, args.traffic_reps)):
+            for b in bufs:
+                b.next_slot()
+                b.pack(ebs, stream)
+                b.conv(ebs, stream, args.variant)
+                torch.cuda.synchronize()
+        print(json.dumps({"traffic_pass": True, "passes": max(1, args.traffic_reps), "copy_bytes": n, "cases": len(bufs), "source_digest": source_digest()}))
         return
 
     def step():

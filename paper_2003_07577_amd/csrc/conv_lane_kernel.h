@@ -34,6 +34,7 @@ struct LaneShape {
     int ntiles;         // N*OH * runs * kgroups
     int xcd_chunk;      // ceil(work-groups / 8): work-groups of one die
     int per_channel;
+    unsigned act_bytes, wgt_bytes;      // sizes of the packed operands
     FastDiv div_kgroups, div_runs, div_oh;
 };
 
@@ -45,6 +46,48 @@ __device__ __forceinline__ uint32_t lane_bcnt_acc(uint32_t x, uint32_t acc)
 }
 
 __device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
+// Per-lane memory accesses go through buffer instructions: address = descriptor base + per-lane byte offset
+// (a register that never changes) + wave-uniform byte offset (a scalar register).  Nothing of the address
+// arithmetic then runs on the vector unit, which this kernel keeps for AND + bitcount.
+constexpr unsigned kRawBufferFlags = 0x00020000u;      // untyped 32-bit data (gfx9 family)
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t raw_buffer(const void *base, unsigned bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, (int)kRawBufferFlags);
+}
+
+template <int NW> struct BufferLoad;
+template <> struct BufferLoad<1> {
+    static __device__ __forceinline__ void run(uint32_t (&q)[1], __amdgpu_buffer_rsrc_t r, unsigned lane_bytes, unsigned uni_bytes)
+    {
+        q[0] = __builtin_amdgcn_raw_buffer_load_b32(r, (int)lane_bytes, (int)uni_bytes, 0);
+    }
+};
+template <> struct BufferLoad<2> {
+    static __device__ __forceinline__ void run(uint32_t (&q)[2], __amdgpu_buffer_rsrc_t r, unsigned lane_bytes, unsigned uni_bytes)
+    {
+        typedef uint32_t v2 __attribute__((ext_vector_type(2)));
+        const v2 v = __builtin_amdgcn_raw_buffer_load_b64(r, (int)lane_bytes, (int)uni_bytes, 0);
+        q[0] = v.x; q[1] = v.y;
+    }
+};
+template <> struct BufferLoad<3> {
+    static __device__ __forceinline__ void run(uint32_t (&q)[3], __amdgpu_buffer_rsrc_t r, unsigned lane_bytes, unsigned uni_bytes)
+    {
+        typedef uint32_t v3 __attribute__((ext_vector_type(3)));
+        const v3 v = __builtin_amdgcn_raw_buffer_load_b96(r, (int)lane_bytes, (int)uni_bytes, 0);
+        q[0] = v.x; q[1] = v.y; q[2] = v.z;
+    }
+};
+template <> struct BufferLoad<4> {
+    static __device__ __forceinline__ void run(uint32_t (&q)[4], __amdgpu_buffer_rsrc_t r, unsigned lane_bytes, unsigned uni_bytes)
+    {
+        typedef uint32_t v4 __attribute__((ext_vector_type(4)));
+        const v4 v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)lane_bytes, (int)uni_bytes, 0);
+        q[0] = v.x; q[1] = v.y; q[2] = v.z; q[3] = v.w;
+    }
+};
 
 template <int KW, int KA, int P, int ST>
 __global__ void __launch_bounds__(256)
@@ -79,6 +122,7 @@ bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
     const int kc = k < sh.K ? k : sh.K - 1;
     // byte offset of the lane's channel in the packed weights
     const unsigned qlane = (unsigned)(((kc / kWgtGroup) * (FS * FS) * sh.cw * kWgtGroup + (kc % kWgtGroup)) * KW) * 4u;
+    const __amdgpu_buffer_rsrc_t wbuf = raw_buffer(wgt, sh.wgt_bytes);
     const int ci = sh.per_channel ? kc : 0;
     const float sc = scale[ci];
     const float of = offset ? offset[ci] : 0.0f;
@@ -90,6 +134,24 @@ bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
     const unsigned x_rwrap = (unsigned)sh.Wp * KA - (unsigned)(sh.cw - 1) * x_wstep;   // first word of the next filter row
     const unsigned q_rwrap = (unsigned)((FS - 1) * sh.cw * QSTEP + QSTEP);
     const unsigned q_tap = (unsigned)(sh.cw * QSTEP);
+    // Every step's input piece lies in another part of memory (steps go over words and filter rows), and a
+    // step's scalar loads are only requested one step ahead: taken alone, each would wait for device memory in
+    // turn.  One vector load per 128-byte line, lane l touching step l's piece, brings all of them into the L2
+    // at once; the values are not used.
+    constexpr int PF_LINES = (XN - 1 + 31) / 32 + 1;
+    uint32_t pf[PF_LINES];
+    {
+        const __amdgpu_buffer_rsrc_t abuf = raw_buffer(act, sh.act_bytes);
+        const int steps = FS * sh.cw;             // <= 64 (launcher)
+        const int sl = (int)lane < steps ? (int)lane : steps - 1;
+        const int r = (sl >= sh.cw) + (sl >= 2 * sh.cw);
+        const unsigned piece = x_off + (unsigned)(sl - r * sh.cw) * x_wstep + (unsigned)(r * sh.Wp * KA);
+#pragma unroll
+        for (int ln = 0; ln < PF_LINES; ++ln) {
+            const int e = ln * 32 < XN - 1 ? ln * 32 : XN - 1;
+            pf[ln] = __builtin_amdgcn_raw_buffer_load_b32(abuf, (int)((piece + (unsigned)e) * 4u), 0, 0);
+        }
+    }
     int w_next = 0;                               // word index of the step the offsets point at
     int left = FS * sh.cw;                        // steps not yet requested
     // request the operands of the step the offsets point at (one scalar piece of input, one per-lane load per
@@ -100,17 +162,7 @@ bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
 #pragma unroll
         for (int e = 0; e < XN; ++e) x[e] = xs[e];
 #pragma unroll
-        for (int s = 0; s < FS; ++s) {
-            const char *qt = reinterpret_cast<const char *>(wgt + (q_off + (unsigned)s * q_tap));
-            typedef uint32_t qvec __attribute__((ext_vector_type(KW), aligned(4)));
-            if constexpr (KW == 1) {
-                q[s][0] = *reinterpret_cast<const uint32_t *>(qt + qlane);
-            } else {
-                const qvec v = *reinterpret_cast<const qvec *>(qt + qlane);
-#pragma unroll
-                for (int i = 0; i < KW; ++i) q[s][i] = v[i];
-            }
-        }
+        for (int s = 0; s < FS; ++s) BufferLoad<KW>::run(q[s], wbuf, qlane, (q_off + (unsigned)s * q_tap) * 4u);
         const bool more = --left > 0;
         const bool wrap = w_next + 1 == sh.cw;
         w_next = wrap ? 0 : w_next + 1;
@@ -159,6 +211,9 @@ bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
         __builtin_amdgcn_sched_barrier(0);
     }
 
+#pragma unroll
+    for (int ln = 0; ln < PF_LINES; ++ln) asm volatile("" ::"v"(pf[ln]));     // keeps the touching loads
+
     // ---- Eq. 14 and the affine epilogue; per position a wave writes 64 consecutive values
     if (k < sh.K) {
         int32_t acc[P];
@@ -169,16 +224,21 @@ bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
             for (int c = 0; c < NCLS; ++c) v += cls[p][c] << c;
             acc[p] = (int32_t)v;
         }
+        // descriptors that start at the wave's first output value and end after its last one (the range check
+        // counts the scalar offset too); the lane offset selects the channel, the scalar offset the position
         const size_t o0 = ((size_t)grow * sh.OW + ow0) * sh.K + (size_t)(kg * 64);
-        char *dst_i = reinterpret_cast<char *>(acc_out + o0);
+        const unsigned prow = (unsigned)sh.K * 4u;
+        const unsigned span = (unsigned)(P - 1) * prow + (unsigned)(sh.K - kg * 64 < 64 ? sh.K - kg * 64 : 64) * 4u;
+        const __amdgpu_buffer_rsrc_t ibuf = raw_buffer(acc_out + o0, span);
 #pragma unroll
         for (int p = 0; p < P; ++p)
-            *reinterpret_cast<int32_t *>(dst_i + (size_t)(p * sh.K) * 4 + lane4) = acc[p];
+            __builtin_amdgcn_raw_buffer_store_b32((uint32_t)acc[p], ibuf, (int)lane4, (int)((unsigned)p * prow), 0);
         if (out_f32) {
-            char *dst_f = reinterpret_cast<char *>(out_f32 + o0);
+            const __amdgpu_buffer_rsrc_t fbuf = raw_buffer(out_f32 + o0, span);
 #pragma unroll
             for (int p = 0; p < P; ++p)
-                *reinterpret_cast<float *>(dst_f + (size_t)(p * sh.K) * 4 + lane4) = fmaf((float)acc[p], sc, of);
+                __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, fmaf((float)acc[p], sc, of)), fbuf,
+                                                      (int)lane4, (int)((unsigned)p * prow), 0);
         }
     }
 }
@@ -195,7 +255,8 @@ template <int KW, int KA, int P, int ST>
 static int launch_lane_cfg(const ConvArgs &a)
 {
     if (a.wtop || a.next) return EBS_ERR_UNSUPPORTED;
-    if (a.R != 3 || a.S != 3 || a.stride != ST || a.pad > kActBorder || a.OW < P || (a.cw & 1)) return EBS_ERR_UNSUPPORTED;
+    if (a.R != 3 || a.S != 3 || a.stride != ST || a.pad > kActBorder || a.OW < P || (a.cw & 1) || a.cw > 20) return EBS_ERR_UNSUPPORTED;
+    constexpr int FSZ = 9;
     LaneShape sh{};
     sh.K = a.K; sh.cw = a.cw; sh.OH = a.OH; sh.OW = a.OW;
     sh.Wp = a.W + 2 * kActBorder;
@@ -208,6 +269,11 @@ static int launch_lane_cfg(const ConvArgs &a)
     if (ntiles > (1LL << 30)) return EBS_ERR_UNSUPPORTED;
     sh.ntiles = (int)ntiles;
     sh.per_channel = a.per_channel;
+    const size_t act_bytes = (size_t)sh.total_pos * a.cw * KA * sizeof(uint32_t);
+    const size_t wgt_bytes = (size_t)((a.K + kWgtGroup - 1) / kWgtGroup) * kWgtGroup * FSZ * a.cw * KW * sizeof(uint32_t);
+    if (act_bytes >= (1ull << 31) || wgt_bytes >= (1ull << 31)) return EBS_ERR_UNSUPPORTED;   // 32-bit byte offsets
+    sh.act_bytes = (unsigned)act_bytes;
+    sh.wgt_bytes = (unsigned)wgt_bytes;
     sh.div_kgroups = make_fastdiv((uint32_t)sh.kgroups);
     sh.div_runs = make_fastdiv((uint32_t)sh.runs);
     sh.div_oh = make_fastdiv((uint32_t)a.OH);
