@@ -13,8 +13,8 @@ EBS_LANE_PAIRS(EBS_DECL)
 #undef EBS_DECL
 
 // sel: 0 = large runs of positions, 1 = small runs.
-// EBS_ERR_UNSUPPORTED for anything but 3x3 filters with pad <= 1, stride 1 or 2, bitwidths up to 4, an even
-// number of 32-channel words, unsigned weights, and output rows at least one run long.
+// EBS_ERR_UNSUPPORTED for anything but 3x3 (pad <= 1) and 1x1 filters, stride 1 or 2, bitwidths up to 4, an even
+// number of (filter row, 32-channel word) steps up to 64, unsigned weights, and output rows at least one run long.
 int launch_conv_lane(const ConvArgs &a, int sel)
 {
 #define EBS_CASE(kw, ka) case (kw) * 8 + (ka): return launch_lane_pair<kw, ka>(a, sel);
@@ -23,10 +23,11 @@ int launch_conv_lane(const ConvArgs &a, int sel)
     return EBS_ERR_UNSUPPORTED;
 }
 
-// Positions per run of the (k_w, k_a, stride) kernels; mirrors LaneRun in conv_lane_kernel.h.  0 = no kernel.
-int lane_run_length(int kw, int ka, int stride, int sel)
+// Positions per run of the (k_w, k_a, stride, filter size) kernels; mirrors LaneRun in conv_lane_kernel.h.
+// 0 = no kernel.
+int lane_run_length(int kw, int ka, int stride, int fs, int sel)
 {
-    if (kw < 1 || kw > 4 || ka < 1 || ka > 4) return 0;
+    if (kw < 1 || kw > 4 || ka < 1 || ka > 4 || (fs != 1 && fs != 3)) return 0;
     const int ncls = kw + ka - 1;
     if (stride == 1) return sel == 0 ? ((ka <= 2 && ncls <= 4) ? 14 : 7) : 7;
     if (stride == 2) return sel == 0 ? (ka <= 2 ? 7 : 4) : 4;

@@ -1,4 +1,4 @@
-// AND + bitcount convolution, "channel per lane" arrangement, for 3x3 filters (paper Sec. 3
+// AND + bitcount convolution, "channel per lane" arrangement, for 3x3 and 1x1 filters (paper Sec. 3
 // Eq. 2; Sec. 4.3 Eq. 13-14 fused into one kernel as in the tiled kernel: the bit-plane partial
 // products stay in registers, one accumulator per shift class i+j).
 //
@@ -6,7 +6,7 @@
 //  * a lane owns ONE output channel; a wave owns 64 consecutive channels x a run of P consecutive
 //    output positions of one output row (a "tile").
 //  * activation words are wave-uniform.  The packed input is [word][position][plane] over the
-//    zero-bordered grid, so the (P-1)*stride + 3 input positions that one filter row of the run
+//    zero-bordered grid, so the (P-1)*stride + filter-size input positions that one filter row of the run
 //    touches are, for one reduction word, ONE contiguous piece of memory: it is fetched with
 //    scalar loads and its words are the scalar operands of v_and_b32.  Weight words are per-lane
 //    vector loads (one load brings the k_w planes of the lane's channel) and are reused for the P
@@ -21,6 +21,8 @@
 #include "ebs_internal.h"
 #include "fastdiv.h"
 
+#include <type_traits>
+
 namespace ebs {
 
 struct LaneShape {
@@ -33,6 +35,8 @@ struct LaneShape {
     int kgroups;        // ceil(K / 64)
     int ntiles;         // N*OH * runs * kgroups
     int xcd_chunk;      // ceil(work-groups / 8): work-groups of one die
+    int touch_ahead;    // tiles between a tile and the one whose input it brings into the L2 (multiple of kgroups)
+    int touch_ahead_pos;    // the same in position tiles (touch_ahead / kgroups)
     int per_channel;
     unsigned act_bytes, wgt_bytes;      // sizes of the packed operands
     FastDiv div_kgroups, div_runs, div_oh;
@@ -42,6 +46,14 @@ __device__ __forceinline__ uint32_t lane_bcnt_acc(uint32_t x, uint32_t acc)
 {
     uint32_t d;
     asm("v_bcnt_u32_b32 %0, %1, %2" : "=v"(d) : "v"(x), "v"(acc));
+    return d;
+}
+
+// bitcount(x) alone: what the first product of an accumulator uses, so that accumulators need no clearing
+__device__ __forceinline__ uint32_t lane_bcnt_first(uint32_t x)
+{
+    uint32_t d;
+    asm("v_bcnt_u32_b32 %0, %1, 0" : "=v"(d) : "v"(x));
     return d;
 }
 
@@ -89,16 +101,15 @@ template <> struct BufferLoad<4> {
     }
 };
 
-template <int KW, int KA, int P, int ST>
+template <int KW, int KA, int P, int ST, int FS>
 __global__ void __launch_bounds__(256)
 bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
              const float *__restrict__ scale, const float *__restrict__ offset,
              int32_t *__restrict__ acc_out, float *__restrict__ out_f32, const LaneShape sh)
 {
     constexpr int NCLS = KW + KA - 1;
-    constexpr int NSEG = (P - 1) * ST + 3;        // input positions one filter row of the run touches
+    constexpr int NSEG = (P - 1) * ST + FS;       // input positions one filter row of the run touches
     constexpr int XN = NSEG * KA;                 // dwords of one step's input piece
-    constexpr int FS = 3;
     constexpr int QSTEP = kWgtGroup * KW;         // weights [k/16][tap][word][k%16][plane]: dwords per (tap, word)
 
     // ---- this wave's tile: dies take contiguous runs of work-groups (work-groups are dealt to the dies
@@ -134,23 +145,41 @@ bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
     const unsigned x_rwrap = (unsigned)sh.Wp * KA - (unsigned)(sh.cw - 1) * x_wstep;   // first word of the next filter row
     const unsigned q_rwrap = (unsigned)((FS - 1) * sh.cw * QSTEP + QSTEP);
     const unsigned q_tap = (unsigned)(sh.cw * QSTEP);
-    // Every step's input piece lies in another part of memory (steps go over words and filter rows), and a
-    // step's scalar loads are only requested one step ahead: taken alone, each would wait for device memory in
-    // turn.  One vector load per 128-byte line, lane l touching step l's piece, brings all of them into the L2
-    // at once; the values are not used.
+    // Every step's input piece lies in another part of memory (steps go over words and filter rows), a step's
+    // scalar loads are only requested one step ahead, and the input is read straight from device memory: taken
+    // alone, each step would wait for it in turn.  Vector loads whose values are not used bring the pieces into
+    // the L2 beforehand, one lane per step and 128-byte line:
+    //  * the first tiles of a die (nothing ran before them) touch their own pieces,
+    //  * every tile touches the pieces of the tile that the die starts `touch_ahead` tiles later - about one
+    //    generation of resident waves - so that tile finds them in the L2 when it starts.
     constexpr int PF_LINES = (XN - 1 + 31) / 32 + 1;
-    uint32_t pf[PF_LINES];
-    {
-        const __amdgpu_buffer_rsrc_t abuf = raw_buffer(act, sh.act_bytes);
+    const __amdgpu_buffer_rsrc_t abuf = raw_buffer(act, sh.act_bytes);
+    auto touch = [&](unsigned piece0, uint32_t (&pf)[PF_LINES]) {
         const int steps = FS * sh.cw;             // <= 64 (launcher)
         const int sl = (int)lane < steps ? (int)lane : steps - 1;
         const int r = (sl >= sh.cw) + (sl >= 2 * sh.cw);
-        const unsigned piece = x_off + (unsigned)(sl - r * sh.cw) * x_wstep + (unsigned)(r * sh.Wp * KA);
+        const unsigned piece = piece0 + (unsigned)(sl - r * sh.cw) * x_wstep + (unsigned)(r * sh.Wp * KA);
 #pragma unroll
         for (int ln = 0; ln < PF_LINES; ++ln) {
             const int e = ln * 32 < XN - 1 ? ln * 32 : XN - 1;
             pf[ln] = __builtin_amdgcn_raw_buffer_load_b32(abuf, (int)((piece + (unsigned)e) * 4u), 0, 0);
         }
+    };
+    uint32_t pf_own[PF_LINES], pf_ahead[PF_LINES];
+    const int die_tile = (int)(blockIdx.x >> 3) * 4 + wave;           // index among the die's tiles
+    const bool touch_own = die_tile < sh.touch_ahead && FS * sh.cw > 2;   // (two steps are requested at once anyway)
+    if (touch_own) touch(x_off, pf_own);
+    const bool touch_next = kg == 0 && die_tile + sh.touch_ahead < sh.xcd_chunk * 4 && tile + sh.touch_ahead < sh.ntiles;
+    if (touch_next) {
+        // touch_ahead is a multiple of the channel groups: the tile ahead is channel group 0 of its positions
+        const int ptile_a = ptile + sh.touch_ahead_pos;
+        const int grow_a = (int)fd_div((uint32_t)ptile_a, sh.div_runs);
+        const int run_a = ptile_a - grow_a * sh.runs;
+        const int n_a = (int)fd_div((uint32_t)grow_a, sh.div_oh);
+        const int oh_a = grow_a - n_a * sh.OH;
+        int ow_a = run_a * P;
+        if (ow_a > sh.OW - P) ow_a = sh.OW - P;
+        touch((unsigned)uni((n_a * sh.plane_pos + (oh_a * ST + sh.origin) * sh.Wp + ow_a * ST + sh.origin) * KA), pf_ahead);
     }
     int w_next = 0;                               // word index of the step the offsets point at
     int left = FS * sh.cw;                        // steps not yet requested
@@ -171,12 +200,10 @@ bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
     };
 
     uint32_t cls[P][NCLS];
-#pragma unroll
-    for (int p = 0; p < P; ++p)
-#pragma unroll
-        for (int c = 0; c < NCLS; ++c) cls[p][c] = 0u;
-    // Eq. 2 / Eq. 13 on one (filter row, word): the three taps of the row for the P positions
-    auto mac = [&](const uint32_t (&x)[XN], const uint32_t (&q)[FS][KW]) {
+    // Eq. 2 / Eq. 13 on one (filter row, word): the taps of the row for the P positions.  The very first step
+    // writes every accumulator before it adds to it (shift class c first occurs at tap 0 with the smallest i).
+    auto mac = [&](const uint32_t (&x)[XN], const uint32_t (&q)[FS][KW], auto first_step) {
+        constexpr bool FIRST = decltype(first_step)::value;
 #pragma unroll
         for (int s = 0; s < FS; ++s)
 #pragma unroll
@@ -184,35 +211,58 @@ bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
 #pragma unroll
                 for (int i = 0; i < KW; ++i)
 #pragma unroll
-                    for (int j = 0; j < KA; ++j)
-                        cls[p][i + j] = lane_bcnt_acc(q[s][i] & x[(p * ST + s) * KA + j], cls[p][i + j]);
+                    for (int j = 0; j < KA; ++j) {
+                        const uint32_t v = q[s][i] & x[(p * ST + s) * KA + j];
+                        if (FIRST && s == 0 && (i == 0 || j == KA - 1))
+                            cls[p][i + j] = lane_bcnt_first(v);
+                        else
+                            cls[p][i + j] = lane_bcnt_acc(v, cls[p][i + j]);
+                    }
     };
+    using first_t = std::integral_constant<bool, true>;
+    using later_t = std::integral_constant<bool, false>;
 
-    // two steps per trip (the number of steps, 3 * words, is even for an even number of words; the launcher
-    // sends other shapes elsewhere); each step's operands are requested one step ahead
-    uint32_t xa[XN], xb[XN], qa[FS][KW], qb[FS][KW];
-    issue(xa, qa);
-    const int trips = (FS * sh.cw) >> 1;
+    // Each step's operands are requested one step ahead; the loop takes two steps per trip (the launcher admits
+    // only shapes whose number of steps, filter rows * words, is even).
     // Scalar loads can only be waited for all at once.  A step therefore first waits for its own input piece
     // (requested one step ago), then requests the next step's, then multiplies: the wait the multiplication needs
     // would otherwise also cover the request just made.
-    for (int t = 0; t < trips; ++t) {
-        __builtin_amdgcn_s_waitcnt(0xC07F);       // lgkmcnt(0)
+    uint32_t xa[XN], xb[XN], qa[FS][KW], qb[FS][KW];
+    const int trips = (FS * sh.cw) >> 1;
+    issue(xa, qa);
+    __builtin_amdgcn_s_waitcnt(0xC07F);           // lgkmcnt(0)
+    __builtin_amdgcn_sched_barrier(0);
+    issue(xb, qb);
+    __builtin_amdgcn_sched_barrier(0);
+    mac(xa, qa, first_t{});
+    __builtin_amdgcn_sched_barrier(0);
+    for (int t = 1; t < trips; ++t) {
+        __builtin_amdgcn_s_waitcnt(0xC07F);
         __builtin_amdgcn_sched_barrier(0);
-        issue(xb, qb);
+        issue(xa, qa);
         __builtin_amdgcn_sched_barrier(0);
-        mac(xa, qa);
+        mac(xb, qb, later_t{});
         __builtin_amdgcn_sched_barrier(0);
         __builtin_amdgcn_s_waitcnt(0xC07F);
         __builtin_amdgcn_sched_barrier(0);
-        issue(xa, qa);                            // (the last trip re-requests the last step: never used)
+        issue(xb, qb);
         __builtin_amdgcn_sched_barrier(0);
-        mac(xb, qb);
+        mac(xa, qa, later_t{});
         __builtin_amdgcn_sched_barrier(0);
     }
+    __builtin_amdgcn_s_waitcnt(0xC07F);
+    __builtin_amdgcn_sched_barrier(0);
+    mac(xb, qb, later_t{});
 
+    // (keeps the touching loads)
+    if (touch_own) {
 #pragma unroll
-    for (int ln = 0; ln < PF_LINES; ++ln) asm volatile("" ::"v"(pf[ln]));     // keeps the touching loads
+        for (int ln = 0; ln < PF_LINES; ++ln) asm volatile("" ::"v"(pf_own[ln]));
+    }
+    if (touch_next) {
+#pragma unroll
+        for (int ln = 0; ln < PF_LINES; ++ln) asm volatile("" ::"v"(pf_ahead[ln]));
+    }
 
     // ---- Eq. 14 and the affine epilogue; per position a wave writes 64 consecutive values
     if (k < sh.K) {
@@ -244,19 +294,21 @@ bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
 }
 
 // Positions per run: the large choice where accumulators (P * shift classes) and the scalar registers of the
-// input pieces (two buffers of ((P-1)*stride + 3) * k_a) allow it, and a small one for narrow rows.
-template <int KW, int KA, int ST> struct LaneRun {
+// input pieces (two buffers of ((P-1)*stride + filter size) * k_a) allow it, and a small one for narrow rows.
+template <int KW, int KA, int ST, int FS = 3> struct LaneRun {
     static constexpr int NCLS = KW + KA - 1;
     static constexpr int BIG = ST == 1 ? ((KA <= 2 && NCLS <= 4) ? 14 : 7) : (KA <= 2 ? 7 : 4);
     static constexpr int SMALL = ST == 1 ? 7 : 4;
 };
 
-template <int KW, int KA, int P, int ST>
+template <int KW, int KA, int P, int ST, int FS>
 static int launch_lane_cfg(const ConvArgs &a)
 {
     if (a.wtop || a.next) return EBS_ERR_UNSUPPORTED;
-    if (a.R != 3 || a.S != 3 || a.stride != ST || a.pad > kActBorder || a.OW < P || (a.cw & 1) || a.cw > 20) return EBS_ERR_UNSUPPORTED;
-    constexpr int FSZ = 9;
+    if (a.R != FS || a.S != FS || a.stride != ST || a.pad > kActBorder || a.OW < P) return EBS_ERR_UNSUPPORTED;
+    // the loop takes two steps (filter row, word) per trip; one lane per step touches the step's input piece
+    if (((FS * a.cw) & 1) || FS * a.cw > 64) return EBS_ERR_UNSUPPORTED;
+    constexpr int FSZ = FS * FS;
     LaneShape sh{};
     sh.K = a.K; sh.cw = a.cw; sh.OH = a.OH; sh.OW = a.OW;
     sh.Wp = a.W + 2 * kActBorder;
@@ -283,23 +335,34 @@ static int launch_lane_cfg(const ConvArgs &a)
     if (!dev->gfx950) return EBS_ERR_UNSUPPORTED;       // run lengths and die numbering are gfx950's
     const long long wgs = (ntiles + 3) / 4;
     sh.xcd_chunk = (int)((wgs + 7) / 8);
-    hipLaunchKernelGGL((bd_conv_lane<KW, KA, P, ST>), dim3((unsigned)(sh.xcd_chunk * 8)), dim3(256), 0, a.stream,
+    // one generation of resident waves of a die: 32 compute units x 4 SIMDs x 8 waves
+    sh.touch_ahead_pos = (dev->cus / 8 * 32 + sh.kgroups - 1) / sh.kgroups;
+    sh.touch_ahead = sh.touch_ahead_pos * sh.kgroups;
+    hipLaunchKernelGGL((bd_conv_lane<KW, KA, P, ST, FS>), dim3((unsigned)(sh.xcd_chunk * 8)), dim3(256), 0, a.stream,
                        a.act, a.wgt, a.scale, a.offset, a.acc, a.out, sh);
     return hip_ok(hipGetLastError());
 }
 
 // sel: 0 = large runs, 1 = small runs
+template <int KW, int KA, int FS>
+static int launch_lane_fs(const ConvArgs &a, int sel)
+{
+    if (a.stride == 1) {
+        if (sel == 0) return launch_lane_cfg<KW, KA, LaneRun<KW, KA, 1, FS>::BIG, 1, FS>(a);
+        return launch_lane_cfg<KW, KA, LaneRun<KW, KA, 1, FS>::SMALL, 1, FS>(a);
+    }
+    if (a.stride == 2) {
+        if (sel == 0) return launch_lane_cfg<KW, KA, LaneRun<KW, KA, 2, FS>::BIG, 2, FS>(a);
+        return launch_lane_cfg<KW, KA, LaneRun<KW, KA, 2, FS>::SMALL, 2, FS>(a);
+    }
+    return EBS_ERR_UNSUPPORTED;
+}
+
 template <int KW, int KA>
 static int launch_lane_pair_impl(const ConvArgs &a, int sel)
 {
-    if (a.stride == 1) {
-        if (sel == 0) return launch_lane_cfg<KW, KA, LaneRun<KW, KA, 1>::BIG, 1>(a);
-        return launch_lane_cfg<KW, KA, LaneRun<KW, KA, 1>::SMALL, 1>(a);
-    }
-    if (a.stride == 2) {
-        if (sel == 0) return launch_lane_cfg<KW, KA, LaneRun<KW, KA, 2>::BIG, 2>(a);
-        return launch_lane_cfg<KW, KA, LaneRun<KW, KA, 2>::SMALL, 2>(a);
-    }
+    if (a.R == 3 && a.S == 3) return launch_lane_fs<KW, KA, 3>(a, sel);
+    if (a.R == 1 && a.S == 1) return launch_lane_fs<KW, KA, 1>(a, sel);
     return EBS_ERR_UNSUPPORTED;
 }
 

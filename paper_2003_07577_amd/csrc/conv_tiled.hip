@@ -49,7 +49,7 @@ static int run_fs(const ConvArgs &a, int v)
 }
 
 int launch_conv_lane(const ConvArgs &a, int sel);
-int lane_run_length(int kw, int ka, int stride, int sel);
+int lane_run_length(int kw, int ka, int stride, int fs, int sel);
 
 static int run_variant(const ConvArgs &a, int v)
 {
@@ -124,7 +124,7 @@ int launch_conv_tiled(const ConvArgs &a, int variant)
     const long long positions = (long long)a.N * a.OH * a.OW;
     const int slot = ch_slot(a.cw);
     const int rs = a.R * a.S;
-    int order[9];
+    int order[12];
     int n = 0;
     // Channel-per-lane kernel (3x3 filters): no LDS, scalar position arithmetic, direct 256-byte stores.  It wins
     // where the per-work-group costs of the tiled kernel weigh most: few plane pairs (short kernels), and the
@@ -135,7 +135,7 @@ int launch_conv_tiled(const ConvArgs &a, int variant)
         const int pairs = a.kw * a.ka;
         if (pairs <= 4 || (a.cw == 2 && pairs <= 9 && !(a.ka == 4 && a.kw >= 3))) {
             // small runs where the large ones leave fewer than six tiles per SIMD and divide the row
-            const int big = lane_run_length(a.kw, a.ka, a.stride, 0), small = lane_run_length(a.kw, a.ka, a.stride, 1);
+            const int big = lane_run_length(a.kw, a.ka, a.stride, a.R, 0), small = lane_run_length(a.kw, a.ka, a.stride, a.R, 1);
             int sel = 0;
             if (big > 0 && small > 0 && a.OW >= big) {
                 const long long tiles_big = (long long)a.N * a.OH * ((a.OW + big - 1) / big) * ((a.K + 63) / 64);
@@ -146,6 +146,16 @@ int launch_conv_tiled(const ConvArgs &a, int variant)
             order[n++] = V_LANE + sel;
             order[n++] = V_LANE + 1 - sel;
         }
+    }
+    // 1x1 filters: the same kernel with the short runs (the long ones were slower on every shape tried) wherever
+    // the reduction has at least eight words, and at nine plane pairs on shorter ones; layers with a short
+    // reduction and fewer pairs are bound by their output writes and do as well or better with the wide tiles.
+    // Measured on the ResNet-50 bottleneck shapes at (2,4), (3,3), (4,2): -3..-10 % (256->64 @56x56), -10 %
+    // (1024->256 @14x14), -7..-10 % (256->1024 @14x14), -17 % (64->256 @56x56 at (3,3)).
+    if (rs == 1 && a.kw <= 4 && a.ka <= 4 && !a.wtop && positions >= 8192 && (a.cw & 1) == 0 && a.K % 64 == 0 &&
+        (a.cw >= 8 || a.kw * a.ka >= 8)) {
+        order[n++] = V_LANE + 1;
+        order[n++] = V_LANE;
     }
     // reduction split: 8 channels per wave for one-bit weights with 3-4 bit activations (4 would leave too
     // little arithmetic per step), else the 16-register tiles

@@ -22,6 +22,8 @@ VARIANT_GEOS = [  # N, C, H, W, K, R, S, stride, pad
     (2, 33, 8, 8, 3, 5, 5, 1, 2),         # 5x5 filter, pad 2
     (1, 256, 7, 7, 70, 3, 3, 1, 1),       # deep reduction
     (2, 40, 10, 9, 33, 3, 2, 3, 0),       # asymmetric filter, stride 3, no pad
+    (2, 64, 9, 15, 70, 1, 1, 1, 0),       # 1x1, two words, K ragged vs 64
+    (2, 128, 16, 18, 64, 1, 1, 2, 0),     # 1x1 stride 2, four words
 ]
 MUST_ACCEPT = [
     {"p4.tile32.ch2", "k4.tile16.ch2", "k4.tile16.ch1", "k4.tile32.ch2"},
@@ -30,9 +32,12 @@ MUST_ACCEPT = [
     set(),                                 # pad 2 exceeds the stored zero ring: the per-output kernel only
     {"r4.tile16.ch4", "k4.tile16.ch4", "p4.tile32.ch4"},
     {"p4.tile32.ch2", "k4.tile16.ch2"},
+    {"p4.tile32.ch2", "k4.tile16.ch2"},
+    {"p4.tile32.ch2", "k4.tile16.ch4"},
 ]
-# the channel-per-lane kernel (3x3 filters, bitwidths up to four): shapes whose rows hold a short run
-MUST_ACCEPT_LANE = [{"lane.small"}, {"lane.small"}, set(), set(), {"lane.small"}, set()]
+# the channel-per-lane kernel (3x3 and 1x1 filters, bitwidths up to four, an even number of reduction steps):
+# shapes whose rows hold a short run
+MUST_ACCEPT_LANE = [{"lane.small"}, {"lane.small"}, set(), set(), {"lane.small"}, set(), {"lane.small"}, {"lane.small"}]
 
 
 def geometry(inp, stride, pad):
