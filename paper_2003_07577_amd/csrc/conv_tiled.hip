@@ -127,13 +127,22 @@ int launch_conv_tiled(const ConvArgs &a, int variant)
     int order[12];
     int n = 0;
     // Channel-per-lane kernel (3x3 filters): no LDS, scalar position arithmetic, direct 256-byte stores.  It wins
-    // where the per-work-group costs of the tiled kernel weigh most: few plane pairs (short kernels), and the
-    // 64-channel layers with their short reductions; not on the deepest layers (few positions: too few tiles), and
-    // not when many of a wave's 64 channel lanes would idle.  Measured on the ResNet-18 shapes, all 16 pairs.
-    if (rs == 9 && a.R == 3 && a.kw <= 4 && a.ka <= 4 && !a.wtop && positions >= 8192 && (a.cw & 1) == 0 &&
-        (a.K % 64 == 0 || a.K >= 256)) {
+    // where the per-work-group costs of the tiled kernel weigh most - few plane pairs (short kernels), short
+    // reductions - and loses on the deepest stride-1 layer (few positions: too few tiles), at the highest
+    // bitwidths of the layers with many positions, and when many of a wave's 64 channel lanes would idle.
+    // Measured on the ResNet-18 shapes, all 16 pairs, both kernels forced in turn.
+    if (rs == 9 && a.R == 3 && a.kw <= 4 && a.ka <= 4 && !a.wtop && (a.cw & 1) == 0 && (a.K % 64 == 0 || a.K >= 256)) {
         const int pairs = a.kw * a.ka;
-        if (pairs <= 4 || (a.cw == 2 && pairs <= 9 && !(a.ka == 4 && a.kw >= 3))) {
+        bool use = false;
+        if (positions >= 8192) {
+            if (a.stride == 1)
+                use = pairs <= 4 || (pairs <= 9 && !(a.ka == 4 && a.kw >= 3)) || positions < 16384;
+            else
+                use = pairs <= 8;
+        } else if (positions >= 3072 && a.stride == 2) {
+            use = pairs <= 6;
+        }
+        if (use) {
             // small runs where the large ones leave fewer than six tiles per SIMD and divide the row
             const int big = lane_run_length(a.kw, a.ka, a.stride, a.R, 0), small = lane_run_length(a.kw, a.ka, a.stride, a.R, 1);
             int sel = 0;
