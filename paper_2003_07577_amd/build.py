@@ -24,6 +24,7 @@ FLAGS = [
 
 INST = "conv_tiled_inst.hip"      # compiled once per (k_w, k_a, filter specialisation)
 LANE_INST = "conv_lane_inst.hip"  # compiled once per (k_w, k_a), bitwidths up to 4
+PAIR_INST = "conv_pair_inst.hip"  # compiled once per (k_w, k_a), bitwidths up to 5
 
 
 def jobs_list():
@@ -37,8 +38,11 @@ def jobs_list():
     for kw in range(4, 0, -1):
         for ka in range(4, 0, -1):
             jobs.append((os.path.join(CSRC, LANE_INST), f"conv_lane_w{kw}a{ka}.o", [f"-DEBS_KW={kw}", f"-DEBS_KA={ka}"]))
+    for kw in range(5, 0, -1):
+        for ka in range(5, 0, -1):
+            jobs.append((os.path.join(CSRC, PAIR_INST), f"conv_pair_w{kw}a{ka}.o", [f"-DEBS_KW={kw}", f"-DEBS_KA={ka}"]))
     for src in sorted(glob.glob(os.path.join(CSRC, "*.hip"))):
-        if os.path.basename(src) not in (INST, LANE_INST):
+        if os.path.basename(src) not in (INST, LANE_INST, PAIR_INST):
             jobs.append((src, os.path.basename(src)[:-4] + ".o", []))
     return jobs
 

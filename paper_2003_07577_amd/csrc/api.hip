@@ -7,7 +7,7 @@
 
 namespace ebs {
 int pack_activations(const uint8_t *levels, uint32_t *packed, int N, int H, int W, int C, int bits, hipStream_t st);
-int pack_weights(const uint8_t *levels, uint32_t *packed, int K, int C, int RS, int bits, hipStream_t st);
+int pack_weights(const uint8_t *levels, uint32_t *packed, int K, int C, int R, int S, int bits, hipStream_t st);
 int check_levels(const uint8_t *levels, size_t count, int bits, int32_t *flag, hipStream_t st);
 int launch_conv_mfma_i8(const uint8_t *act, const uint8_t *wgt, const ConvArgs &a);
 
@@ -131,7 +131,9 @@ size_t ebs_packed_weights_bytes(int K, int C, int R, int S, int k_w)
 {
     if (!bits_ok(k_w) || check_wgt_shape(K, C, R, S)) return 0;
     size_t kpad = ((size_t)K + kWgtGroup - 1) / kWgtGroup * kWgtGroup;
-    return kpad * R * S * words_per_pixel(C) * k_w * sizeof(uint32_t);
+    size_t dwords = kpad * R * S * words_per_pixel(C) * k_w;
+    if (has_pair_section(C, R, S)) dwords += kpad * 5 * k_w;
+    return dwords * sizeof(uint32_t);
 }
 
 size_t ebs_packed_activations_bytes(int N, int H, int W, int C, int k_a)
@@ -148,7 +150,7 @@ int ebs_pack_weights(const uint8_t *levels, int K, int C, int R, int S, int k_w,
     int rc = check_wgt_shape(K, C, R, S);
     if (rc) return rc;
     if (!aligned16(levels) || !aligned16(packed)) return EBS_ERR_ALIGN;
-    return pack_weights(levels, (uint32_t *)packed, K, C, R * S, k_w, (hipStream_t)stream);
+    return pack_weights(levels, (uint32_t *)packed, K, C, R, S, k_w, (hipStream_t)stream);
 }
 
 int ebs_pack_activations(const uint8_t *levels, int N, int H, int W, int C, int k_a, void *packed, void *stream)

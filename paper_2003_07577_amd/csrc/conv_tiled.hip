@@ -25,9 +25,10 @@ static const char *const kNames[] = {
     "r4.tile64.ch4", "r4.tile32.ch4", "r4.tile16.ch4",
     "k4.wide.ch2", "k4.wide.ch1", "k4.wide.ch4",
     "lane.big", "lane.small",
+    "pair",
 };
 static constexpr int kNumVariants = sizeof(kNames) / sizeof(kNames[0]);
-enum { V_P4_64 = 0, V_P4_32 = 3, V_K4_64 = 6, V_K4_32 = 9, V_K4_16 = 12, V_R4_64 = 15, V_R4_32 = 16, V_R4_16 = 17, V_K4_WIDE = 18, V_LANE = 21 };
+enum { V_P4_64 = 0, V_P4_32 = 3, V_K4_64 = 6, V_K4_32 = 9, V_K4_16 = 12, V_R4_64 = 15, V_R4_32 = 16, V_R4_16 = 17, V_K4_WIDE = 18, V_LANE = 21, V_PAIR = 23 };
 
 int conv_tiled_variant_count() { return kNumVariants; }
 const char *conv_tiled_variant_name(int v) { return (v >= 0 && v < kNumVariants) ? kNames[v] : "invalid"; }
@@ -54,6 +55,7 @@ int lane_run_length(int kw, int ka, int stride, int fs, int sel);
 static int run_variant(const ConvArgs &a, int v)
 {
     if (v < 0 || v >= kNumVariants) return EBS_ERR_UNSUPPORTED;
+    if (v == V_PAIR) return launch_conv_pair(a);
     if (v >= V_LANE) return launch_conv_lane(a, v - V_LANE);
     if (a.R == 3 && a.S == 3) return run_fs<3>(a, v);     // unrolled 3x3 taps
     return run_fs<0>(a, v);
@@ -100,6 +102,11 @@ int launch_requant_tiled(const ConvArgs &a)
 {
     const long long positions = (long long)a.N * a.OH * a.OW;
     const int rs = a.R * a.S;
+    // 3x3 layers with at most 16 input channels: two taps per word
+    {
+        const int rc = launch_conv_pair(a);
+        if (rc != EBS_ERR_UNSUPPORTED) return rc;
+    }
     int order[4];
     int n = 0;
     if ((rs > 1 || a.kw * a.ka <= 2) && rs * a.cw >= 64 && positions <= 16384 && a.cw % 4 == 0) order[n++] = 3;
@@ -124,8 +131,11 @@ int launch_conv_tiled(const ConvArgs &a, int variant)
     const long long positions = (long long)a.N * a.OH * a.OW;
     const int slot = ch_slot(a.cw);
     const int rs = a.R * a.S;
-    int order[12];
+    int order[13];
     int n = 0;
+    // 3x3 layers with at most 16 input channels: two taps per word (half the AND + bitcount work of the
+    // one-tap-per-word kernels, whose words are half zeros there)
+    if (a.C <= 16 && rs == 9 && a.R == 3 && a.K <= 32) order[n++] = V_PAIR;
     // Channel-per-lane kernel (3x3 filters): no LDS, scalar position arithmetic, direct 256-byte stores.  It wins
     // where the per-work-group costs of the tiled kernel weigh most - few plane pairs (short kernels), short
     // reductions - and loses on the deepest stride-1 layer (few positions: too few tiles), at the highest

@@ -47,6 +47,11 @@ constexpr int kActBorder = 1;
 // run past the end of the last position.
 constexpr int kActTailDwords = 4;
 
+// 3x3 layers with at most 16 input channels: the packed weights end with a section that holds two taps per
+// word, ceil16(K) * 5 * k_w dwords (conv_pair_kernel.h)
+inline bool has_pair_section(int C, int R, int S) { return C <= 16 && R == 3 && S == 3; }
+int launch_conv_pair(const ConvArgs &a);         // EBS_ERR_UNSUPPORTED when the shape is not the pair kernel's
+
 int launch_conv_naive(const ConvArgs &a);
 int launch_requant_naive(const ConvArgs &a);
 int launch_zero_border(uint32_t *packed, int N, int H, int W, int words, int planes, hipStream_t st);

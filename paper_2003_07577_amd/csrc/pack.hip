@@ -15,7 +15,8 @@
 // Weights: uint32 [k / 16][tap = r*S+s][word][k % 16][plane]; output channels
 // beyond K (up to the next multiple of 16) are zero.  One reduction step of a
 // 16-channel group is k_w*16 consecutive words, which a wave can fetch with
-// scalar loads.
+// scalar loads.  3x3 layers with C <= 16 carry a second section behind it with
+// two taps per word (pack_wgt_pairs).
 #include "ebs_internal.h"
 #include "fastdiv.h"
 
@@ -163,6 +164,38 @@ pack_wgt_generic(const uint8_t *__restrict__ levels, uint32_t *__restrict__ pack
     for (int i = 0; i < BITS; ++i) packed[item * BITS + i] = planes[i];
 }
 
+// Second section of the packed weights of 3x3 layers with C <= 16: two taps per word, five words per
+// plane, uint32 [k][word][plane] for k < ceil16(K) (zero beyond K):
+//   word 0..2 = taps (r,0) | (r,1) << 16 for r = 0..2, word 3 = taps (0,2) | (1,2) << 16, word 4 = tap (2,2).
+// One thread per (k, word).
+template <int BITS>
+__global__ void __launch_bounds__(256)
+pack_wgt_pairs(const uint8_t *__restrict__ levels, uint32_t *__restrict__ pairs, int K, int C, int n_items /* Kpad*5 */)
+{
+    const int item = blockIdx.x * blockDim.x + threadIdx.x;
+    if (item >= n_items) return;
+    const int k = item / 5, t5 = item - k * 5;
+    const int tap_lo = t5 < 3 ? 3 * t5 : (t5 == 3 ? 2 : 8);
+    const int tap_hi = t5 < 3 ? 3 * t5 + 1 : (t5 == 3 ? 5 : -1);
+    uint32_t planes[BITS];
+#pragma unroll
+    for (int i = 0; i < BITS; ++i) planes[i] = 0u;
+    if (k < K) {
+        for (int half = 0; half < 2; ++half) {
+            const int tap = half ? tap_hi : tap_lo;
+            if (tap < 0) continue;
+            const uint8_t *src = levels + ((long long)k * 9 + tap) * C;
+            for (int c = 0; c < C; ++c) {
+                const uint32_t lv = src[c];
+#pragma unroll
+                for (int i = 0; i < BITS; ++i) planes[i] |= ((lv >> i) & 1u) << (c + 16 * half);
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < BITS; ++i) pairs[(size_t)item * BITS + i] = planes[i];
+}
+
 __global__ void clear_flag_kernel(int32_t *flag) { *flag = 0; }
 
 __global__ void __launch_bounds__(256)
@@ -193,13 +226,19 @@ static int launch_pack_act(const uint8_t *levels, uint32_t *packed, int N, int H
 }
 
 template <int BITS>
-static int launch_pack_wgt(const uint8_t *levels, uint32_t *packed, int K, int C, int RS, hipStream_t st)
+static int launch_pack_wgt(const uint8_t *levels, uint32_t *packed, int K, int C, int R, int S, hipStream_t st)
 {
+    const int RS = R * S;
     int cw = words_per_pixel(C);
     long long kpad = (long long)((K + kWgtGroup - 1) / kWgtGroup) * kWgtGroup;
     long long items = kpad * RS * cw;
     unsigned blocks = (unsigned)((items + 255) / 256);
     hipLaunchKernelGGL(pack_wgt_generic<BITS>, dim3(blocks), dim3(256), 0, st, levels, packed, K, C, RS, cw, items);
+    if (has_pair_section(C, R, S)) {
+        const int n_items = (int)kpad * 5;
+        hipLaunchKernelGGL(pack_wgt_pairs<BITS>, dim3((unsigned)((n_items + 255) / 256)), dim3(256), 0, st, levels,
+                           packed + items * BITS, K, C, n_items);
+    }
     return hip_ok(hipGetLastError());
 }
 
@@ -215,14 +254,14 @@ int pack_activations(const uint8_t *levels, uint32_t *packed, int N, int H, int 
     return EBS_ERR_BITWIDTH;
 }
 
-int pack_weights(const uint8_t *levels, uint32_t *packed, int K, int C, int RS, int bits, hipStream_t st)
+int pack_weights(const uint8_t *levels, uint32_t *packed, int K, int C, int R, int S, int bits, hipStream_t st)
 {
     switch (bits) {
-        case 1: return launch_pack_wgt<1>(levels, packed, K, C, RS, st);
-        case 2: return launch_pack_wgt<2>(levels, packed, K, C, RS, st);
-        case 3: return launch_pack_wgt<3>(levels, packed, K, C, RS, st);
-        case 4: return launch_pack_wgt<4>(levels, packed, K, C, RS, st);
-        case 5: return launch_pack_wgt<5>(levels, packed, K, C, RS, st);
+        case 1: return launch_pack_wgt<1>(levels, packed, K, C, R, S, st);
+        case 2: return launch_pack_wgt<2>(levels, packed, K, C, R, S, st);
+        case 3: return launch_pack_wgt<3>(levels, packed, K, C, R, S, st);
+        case 4: return launch_pack_wgt<4>(levels, packed, K, C, R, S, st);
+        case 5: return launch_pack_wgt<5>(levels, packed, K, C, R, S, st);
     }
     return EBS_ERR_BITWIDTH;
 }

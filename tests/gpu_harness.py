@@ -24,6 +24,9 @@ VARIANT_GEOS = [  # N, C, H, W, K, R, S, stride, pad
     (2, 40, 10, 9, 33, 3, 2, 3, 0),       # asymmetric filter, stride 3, no pad
     (2, 64, 9, 15, 70, 1, 1, 1, 0),       # 1x1, two words, K ragged vs 64
     (2, 128, 16, 18, 64, 1, 1, 2, 0),     # 1x1 stride 2, four words
+    (3, 16, 12, 10, 16, 3, 3, 1, 1),      # 16 input channels: two taps per word; several tiles, an image boundary inside one
+    (2, 12, 9, 11, 20, 3, 3, 2, 1),       # fewer than 16 input channels, stride 2, K ragged against the 32 channel lanes
+    (1, 7, 6, 5, 3, 3, 3, 1, 0),          # no padding, a single partial tile
 ]
 MUST_ACCEPT = [
     {"p4.tile32.ch2", "k4.tile16.ch2", "k4.tile16.ch1", "k4.tile32.ch2"},
@@ -34,10 +37,37 @@ MUST_ACCEPT = [
     {"p4.tile32.ch2", "k4.tile16.ch2"},
     {"p4.tile32.ch2", "k4.tile16.ch2"},
     {"p4.tile32.ch2", "k4.tile16.ch4"},
+    {"pair", "p4.tile32.ch1"},
+    {"pair", "p4.tile32.ch1"},
+    {"pair", "p4.tile32.ch1"},
 ]
 # the channel-per-lane kernel (3x3 and 1x1 filters, bitwidths up to four, an even number of reduction steps):
 # shapes whose rows hold a short run
-MUST_ACCEPT_LANE = [{"lane.small"}, {"lane.small"}, set(), set(), {"lane.small"}, set(), {"lane.small"}, {"lane.small"}]
+MUST_ACCEPT_LANE = [{"lane.small"}, {"lane.small"}, set(), set(), {"lane.small"}, set(), {"lane.small"}, {"lane.small"},
+                    set(), set(), set()]
+
+
+def unpack_weight_pairs(words, K, C, k_w):
+    """Second section of the packed weights of a 3x3 layer with C <= 16: uint32 [k][5][plane] for k < ceil16(K),
+    two taps per word (low half | high half << 16): words 0..2 = taps (r,0), (r,1); word 3 = taps (0,2), (1,2);
+    word 4 = tap (2,2).  -> levels KRSC rebuilt from it, and every bit that must be zero."""
+    kpad = (K + 15) // 16 * 16
+    first = kpad * 9 * 1 * k_w
+    w = np.asarray(words).view(np.uint32)[first:first + kpad * 5 * k_w].reshape(kpad, 5, k_w)
+    halves = [((0, 0), (0, 1)), ((1, 0), (1, 1)), ((2, 0), (2, 1)), ((0, 2), (1, 2)), ((2, 2), None)]
+    lv = np.zeros((kpad, 3, 3, 16), np.uint8)
+    stray = []
+    for t5, (lo, hi) in enumerate(halves):
+        for half, tap in enumerate((lo, hi)):
+            bits = ((w[:, t5, :, None] >> (np.arange(16, dtype=np.uint32) + 16 * half)) & 1).astype(np.uint8)  # k,plane,c
+            if tap is None:
+                stray.append(bits.reshape(-1))
+                continue
+            for i in range(k_w):
+                lv[:, tap[0], tap[1], :] |= bits[:, i, :] << i
+    stray.append(lv[K:].reshape(-1))
+    stray.append(lv[:K, :, :, C:].reshape(-1))
+    return lv[:K, :, :, :C], np.concatenate(stray)
 
 
 def geometry(inp, stride, pad):
@@ -131,10 +161,11 @@ def unpack_activations(words, N, H, W, C, k_a):
 
 
 def unpack_weights(words, K, C, R, S, k_w):
-    """uint32 [k/16][tap][word][k%16][plane] -> levels KRSC (and the padded remainder)."""
+    """uint32 [k/16][tap][word][k%16][plane] -> levels KRSC (and the padded remainder).  (3x3 layers with at
+    most 16 input channels carry a second section behind this one: unpack_weight_pairs.)"""
     cw = (C + 31) // 32
     kg = (K + 15) // 16
-    w = np.asarray(words).view(np.uint32).reshape(kg, R * S, cw, 16, k_w)
+    w = np.asarray(words).view(np.uint32)[:kg * R * S * cw * 16 * k_w].reshape(kg, R * S, cw, 16, k_w)
     bits = ((w[..., None] >> np.arange(32, dtype=np.uint32)) & 1).astype(np.uint8)  # kg,tap,word,kl,plane,bit
     lv = np.zeros((kg, R * S, cw, 16, 32), np.uint8)
     for i in range(k_w):

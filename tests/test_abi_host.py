@@ -66,6 +66,10 @@ def test_packed_sizes(lib):
     # weights: K rounded up to 16
     assert ebs.ebs_packed_weights_bytes(64, 64, 3, 3, 1) == 64 * 9 * 2 * 4
     assert ebs.ebs_packed_weights_bytes(1000, 2048, 1, 1, 4) == 1008 * 64 * 4 * 4
+    # 3x3 with at most 16 input channels: the ordinary section plus five two-tap words per channel and plane
+    assert ebs.ebs_packed_weights_bytes(20, 16, 3, 3, 3) == (32 * 9 * 3 + 32 * 5 * 3) * 4
+    assert ebs.ebs_packed_weights_bytes(20, 16, 1, 1, 3) == 32 * 1 * 3 * 4
+    assert ebs.ebs_packed_weights_bytes(20, 17, 3, 3, 3) == 32 * 9 * 3 * 4
     for bad in [(0, 8, 8, 16, 2), (1, 8, 8, 16, 0), (1, 8, 8, 16, 6), (1, -1, 8, 16, 2)]:
         assert ebs.ebs_packed_activations_bytes(*bad) == 0
     assert ebs.ebs_packed_weights_bytes(16, 16, 3, 3, 9) == 0

@@ -7,7 +7,7 @@ import pytest
 import ebs_workloads as wl
 import paper_2003_07577_amd as ebs
 from gpu_harness import (MUST_ACCEPT, MUST_ACCEPT_LANE, POISON, VARIANT_GEOS, assert_f32_close, conv, pack, run_case,
-                         unpack_activations, unpack_weights, upload)
+                         unpack_activations, unpack_weight_pairs, unpack_weights, upload)
 
 pytestmark = pytest.mark.gpu
 
@@ -42,7 +42,7 @@ def test_config1_tiny(oracle_mod):
 
 
 # ------------------------------------------------------------------ packing
-@pytest.mark.parametrize("C", [16, 32, 48, 64, 100, 1000])
+@pytest.mark.parametrize("C", [11, 16, 32, 48, 64, 100, 1000])
 @pytest.mark.parametrize("bits", [1, 2, 3, 4, 5])
 def test_pack_roundtrip(C, bits):
     import torch
@@ -62,6 +62,11 @@ def test_pack_roundtrip(C, bits):
     wv, kpad, cpad = unpack_weights(d["pw"].cpu().numpy(), K, C, R, S, bits)
     assert np.array_equal(wv, inp["q"] & mask)
     assert not kpad.any() and not cpad.any()
+    if C <= 16:
+        # 3x3 with at most 16 input channels: the two-taps-per-word section holds the same levels
+        pv, stray = unpack_weight_pairs(d["pw"].cpu().numpy(), K, C, bits)
+        assert np.array_equal(pv, inp["q"] & mask)
+        assert not stray.any(), "unused halves and padding channels of the pair section must be zero"
     # plane population counts against numpy
     words = d["pa"].cpu().numpy().view(np.uint32)[:N * (H + 2) * (W + 2) * ((C + 31) // 32) * bits].reshape(-1, bits)
     for j in range(bits):

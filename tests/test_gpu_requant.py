@@ -48,6 +48,9 @@ GEOS = [  # N, C, H, W, K, R, S, stride, pad
     (1, 256, 7, 7, 96, 3, 3, 1, 1),       # few positions, long reduction: reduction-split kernel
     (2, 256, 6, 6, 50, 3, 3, 1, 1),       # the same with K ragged against the bytes and words of the packed output
     (1, 128, 9, 9, 7, 3, 3, 2, 1),        # reduction-split, K < 8
+    (3, 16, 12, 10, 16, 3, 3, 1, 1),      # 16 input channels: the two-taps-per-word kernel, 16 channel lanes
+    (2, 16, 14, 14, 32, 3, 3, 2, 1),      # the same at stride 2 with 32 channel lanes
+    (2, 9, 7, 9, 21, 3, 3, 1, 0),         # fewer channels, K ragged, no padding
 ]
 
 
