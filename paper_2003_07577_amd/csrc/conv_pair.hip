@@ -14,7 +14,7 @@ EBS_PAIR_PAIRS(EBS_DECL)
 #undef EBS_DECL
 
 // Plain convolution (a.next == null) or the fused re-quantising form.  EBS_ERR_UNSUPPORTED for anything but
-// 3x3 filters with pad <= 1 and stride 1 or 2 on at most 16 input and 32 output channels, unsigned weights.
+// 3x3 filters with pad <= 1 and stride 1 or 2 on at most 16 input and 32 output channels.
 int launch_conv_pair(const ConvArgs &a)
 {
 #define EBS_CASE(kw, ka) case (kw) * 8 + (ka): return launch_pair_pair<kw, ka>(a);

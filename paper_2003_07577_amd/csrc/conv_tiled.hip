@@ -162,8 +162,12 @@ int launch_conv_tiled(const ConvArgs &a, int variant)
             } else {
                 sel = 1;
             }
-            order[n++] = V_LANE + sel;
-            order[n++] = V_LANE + 1 - sel;
+            // the last run of a row is moved left and recomputes the overlap: not where that is over 15 % of the work
+            const int run = sel ? small : big;
+            if (run > 0 && (long long)((a.OW + run - 1) / run) * run * 100 <= (long long)a.OW * 115) {
+                order[n++] = V_LANE + sel;
+                order[n++] = V_LANE + 1 - sel;
+            }
         }
     }
     // 1x1 filters: the same kernel with the short runs (the long ones were slower on every shape tried) wherever

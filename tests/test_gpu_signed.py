@@ -17,6 +17,8 @@ GEOS = [  # N, C, H, W, K, R, S, stride, pad
     (2, 256, 7, 7, 70, 3, 3, 1, 1),        # long reduction, few positions -> R4
     (2, 33, 8, 8, 9, 5, 5, 1, 2),          # pad 2 -> per-output kernel
     (4, 128, 6, 6, 40, 1, 1, 1, 0),        # 1x1
+    (3, 16, 12, 10, 16, 3, 3, 1, 1),       # 16 input channels -> two taps per word, window sums from the pair words
+    (2, 12, 9, 11, 20, 3, 3, 2, 1),        # the same, ragged C and K, stride 2
 ]
 
 
