@@ -264,7 +264,8 @@ int launch_conv_mfma_i8(const uint8_t *act, const uint8_t *wgt, const ConvArgs &
     if (a.C % 64 == 0) {
         // tile choice: wide channel tile when the layer has the channels, deep reduction steps when
         // C allows, and the smaller position tile when the larger one would leave compute units idle
-        const bool nb2 = a.K > 64;
+        // 128-channel tiles only where they still leave at least two work-groups per compute unit
+        const bool nb2 = a.K > 64 && (((long long)total + 63) / 64) * (((long long)a.K + 127) / 128) >= 512;
         const bool kk4 = a.C % 128 == 0;
         const long long big_blocks = (((long long)total + 127) / 128) * (((long long)a.K + (nb2 ? 127 : 63)) / (nb2 ? 128 : 64));
         const bool mb2 = big_blocks >= 1024;
