@@ -213,8 +213,11 @@ def measured_peaks(ebs, torch, dev, stream):
     dst = torch.empty(n, dtype=torch.uint8, device=dev)
     t_copy = min(timed(lambda: ebs.ebs_probe_copy(src, dst, n, 8192, stream), 5) for _ in range(3))
     t_fill = min(timed(lambda: ebs.ebs_probe_copy(None, dst, n, 8192, stream), 5) for _ in range(3))
+    # period of back-to-back launches of a kernel that does next to nothing (one work-group copying 4 KiB):
+    # what every launch of a stream costs at least, whatever the kernel
+    t_empty = min(timed(lambda: ebs.ebs_probe_copy(src, dst, 4096, 1, stream), 200) for _ in range(3))
     return {"alu_binary_tops": round(alu, 1), "hbm_copy_gbs": round(2 * n / t_copy / 1e9, 1),
-            "hbm_fill_gbs": round(n / t_fill / 1e9, 1),
+            "hbm_fill_gbs": round(n / t_fill / 1e9, 1), "launch_period_floor_us": round(t_empty * 1e6, 2),
             "how": "ebs_probe_and_bcnt (register-only AND + accumulating bitcount, 2048 work-groups) and "
                    "ebs_probe_copy on 256 MiB (copy counts read + written bytes; fill = write only)"}
 
@@ -373,7 +376,7 @@ def main():
             "conv_us": round(conv_us, 2), "conv_us_min_batch": round(conv_us_min, 2), "pack_us": round(pack_us, 2),
             "binary_tops": round(tops, 1), "alu_frac": round(tops / PEAK_BINARY_TOPS, 4),
             "conv_hbm_gbs": round(conv_bytes(c) / conv_us / 1e3, 1),
-            "pack_hbm_gbs": round(pack_bytes(c) / pack_us / 1e3, 1),
+            "pack_hbm_gbs": round(pack_bytes(c) / pack_us / 1e3, 1), "pack_bytes": pack_bytes(c),
             "binding_roof": "alu" if t_alu >= t_hbm else "hbm",
             "roof_us": round(max(t_alu, t_hbm), 2),
             "frac_of_binding_roof": round(max(t_alu, t_hbm) / conv_us, 4),
@@ -403,6 +406,15 @@ def main():
         "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(pack_bytes_sum / pack_us_sum / 1e3 / HBM_PEAK_GBS, 4),
         "avg_launch_us": round(pack_us_sum / len(bufs), 2),
     }
+    # large and small inputs apart: below a few MB a launch is as short as the launch period itself
+    for name, sel in (("large_inputs", lambda r: r["pack_bytes"] >= 8 << 20), ("small_inputs", lambda r: r["pack_bytes"] < 8 << 20)):
+        rows = [r for r in table if sel(r)]
+        if rows:
+            us = sum(r["pack_us"] for r in rows)
+            by = sum(r["pack_bytes"] for r in rows)
+            pack_roof[name] = {"cases": len(rows), "avg_launch_us": round(us / len(rows), 2),
+                               "achieved": round(by / us / 1e3, 1), "frac": round(by / us / 1e3 / HBM_PEAK_GBS, 4)}
+    pack_roof["launch_period_floor_us"] = peaks["launch_period_floor_us"]
 
     # ---- measured comparison: the same layers on the int8 matrix cores (no binary decomposition);
     #      its time does not depend on the bitwidths, so each layer shape is timed once

@@ -223,6 +223,7 @@ def test_mfma_i8_comparison_matches_oracle(oracle_mod):
     geos = [  # N, C, H, W, K, R, S, stride, pad
         (2, 64, 20, 20, 40, 3, 3, 1, 1), (3, 96, 9, 11, 130, 3, 3, 2, 1), (1, 32, 13, 7, 5, 1, 1, 1, 0),
         (2, 128, 8, 8, 64, 3, 3, 1, 1), (1, 256, 7, 7, 70, 3, 3, 1, 1), (2, 64, 10, 9, 33, 3, 2, 3, 0),
+        (5, 64, 9, 11, 130, 3, 3, 2, 1), (2, 64, 6, 6, 70, 1, 1, 1, 0), (1, 192, 30, 30, 64, 3, 3, 1, 1),
     ]
     for gi, (N, C, H, W, K, R, S, st, pad) in enumerate(geos):
         inp = wl.random_case(4000 + gi, N, C, H, W, K, R, S, st, pad, 4, 4, per_channel=(gi % 2 == 0), with_offset=True)
