@@ -81,6 +81,10 @@ size_t ebs_packed_activations_bytes(int N, int H, int W, int C, int k_a);
  * once per layer (offline in the paper's deployment flow).
  *   levels_krsc : in,  device, K*R*S*C bytes
  *   packed      : out, device, ebs_packed_weights_bytes(...) bytes
+ * The packed form is opaque: it is what the convolution calls expect for the
+ * same (K, C, R, S, k_w) and nothing else may write it (for 3x3 filters on at
+ * most 16 input channels it holds a second arrangement of the same planes, two
+ * filter taps per 32-bit word, which the size above includes).
  */
 int ebs_pack_weights(const uint8_t *levels_krsc, int K, int C, int R, int S, int k_w,
                      void *packed, void *stream);
