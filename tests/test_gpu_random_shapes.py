@@ -86,3 +86,60 @@ def test_random_shapes_all_entry_points(oracle_mod, block):
         lv, padbits, border = unpack_activations(nxt.cpu().numpy(), N, g["OH"], g["OW"], K, k_next)
         assert np.array_equal(lv, want), tag
         assert not padbits.any() and not border.any(), tag
+
+
+def _draw_lane_or_pair_geometry(rng):
+    """Shapes the channel-per-lane kernel (3x3 / 1x1, an even number of 32-channel words) or the
+    two-taps-per-word kernel (3x3, at most 16 input and 32 output channels) accept."""
+    kind = int(rng.integers(0, 3))
+    if kind == 0:        # channel-per-lane, 3x3
+        R, C, pad, st = 3, 64 * int(rng.integers(1, 4)), int(rng.integers(0, 2)), int(rng.integers(1, 3))
+        K, H, W, N = int(rng.choice([64, 70, 128, 130, 260])), int(rng.integers(5, 24)), int(rng.integers(9, 30)), int(rng.integers(1, 4))
+        bits = (int(rng.integers(1, 5)), int(rng.integers(1, 5)))
+    elif kind == 1:      # channel-per-lane, 1x1
+        R, C, pad, st = 1, 64 * int(rng.integers(1, 7)), 0, int(rng.integers(1, 3))
+        K, H, W, N = int(rng.choice([64, 100, 128, 192])), int(rng.integers(4, 20)), int(rng.integers(8, 30)), int(rng.integers(1, 4))
+        bits = (int(rng.integers(1, 5)), int(rng.integers(1, 5)))
+    else:                # two taps per word
+        R, C, pad, st = 3, int(rng.integers(1, 17)), int(rng.integers(0, 2)), int(rng.integers(1, 3))
+        K, H, W, N = int(rng.integers(1, 33)), int(rng.integers(3, 30)), int(rng.integers(3, 30)), int(rng.integers(1, 7))
+        bits = (int(rng.integers(1, 6)), int(rng.integers(1, 6)))
+    return kind, (N, C, H, W, K, R, R, st, pad), bits
+
+
+@pytest.mark.parametrize("block", range(6))
+def test_random_shapes_forced_lane_and_pair_kernels(oracle_mod, block):
+    """The heuristic sends only large layers to the channel-per-lane kernel; here it and the two-taps-per-word
+    kernel are forced (by variant) on random small shapes and compared with the oracle."""
+    import torch
+    names = {ebs.ebs_conv_variant_name(v): v for v in range(ebs.ebs_conv_variant_count() + 1)}
+    rng = np.random.default_rng(9090 + block)
+    ran = {"lane.big": 0, "lane.small": 0, "pair": 0}
+    for i in range(10):
+        kind, (N, C, H, W, K, R, S, st, pad), (kw, ka) = _draw_lane_or_pair_geometry(rng)
+        if H + 2 * pad < R or W + 2 * pad < S:
+            continue
+        per_channel = bool(rng.integers(0, 2))
+        inp = wl.random_case(int(rng.integers(1 << 30)), N, C, H, W, K, R, S, st, pad, kw, ka,
+                             per_channel=per_channel, with_offset=bool(rng.integers(0, 2)))
+        tag = f"block{block}.{i} N{N} C{C} H{H} W{W} K{K} R{R} s{st} p{pad} w{kw} a{ka}"
+        d = upload(inp, kw, ka, st, pad)
+        pack(d)
+        g = d["g"]
+        ref = oracle_mod.conv2d_levels(inp["a"], inp["q"], st, pad)
+        fref = oracle_mod.dequant(ref, inp["scale"], inp["offset"], inp["per_channel"])
+        for name in (("pair",) if kind == 2 else ("lane.big", "lane.small")):
+            print(f"[case] {tag} {name}", flush=True)
+            d["acc"].fill_(POISON)
+            d["out"].fill_(float("nan"))
+            rc = ebs.ebs_mixed_conv2d_variant(names[name], d["pa"], d["pw"], g["N"], g["C"], g["H"], g["W"], g["K"], g["R"],
+                                              g["S"], st, pad, kw, ka, d["scale"], d["offset"], d["per_channel"], d["acc"],
+                                              d["out"], check=False)
+            if rc == -5:
+                continue                 # e.g. a row shorter than the kernel's run of positions
+            assert rc == 0, (tag, name, rc)
+            torch.cuda.synchronize()
+            ran[name] += 1
+            assert np.array_equal(d["acc"].cpu().numpy(), ref), (tag, name)
+            assert_f32_close(d["out"].cpu().numpy(), fref, ref, inp["scale"], inp["per_channel"])
+    assert ran["pair"] + ran["lane.big"] + ran["lane.small"] >= 6, ran
