@@ -20,6 +20,7 @@
 #pragma once
 #include "ebs_internal.h"
 #include "fastdiv.h"
+#include "requant.h"
 
 #include <type_traits>
 
@@ -40,6 +41,10 @@ struct LaneShape {
     int per_channel;
     unsigned act_bytes, wgt_bytes;      // sizes of the packed operands
     FastDiv div_kgroups, div_runs, div_oh;
+    // fused re-quantisation (REQ kernels): the next layer's quantiser and packed layout
+    float alpha, qs;
+    int k_next, OHn, OWn, cwn, total_next;
+    int ring_total, ring_per_image;     // dwords of the zero ring of the next layer's packed tensor (all images / one)
 };
 
 __device__ __forceinline__ uint32_t lane_bcnt_acc(uint32_t x, uint32_t acc)
@@ -101,11 +106,15 @@ template <> struct BufferLoad<4> {
     }
 };
 
-template <int KW, int KA, int P, int ST, int FS>
+// REQ: instead of the int32 / fp32 outputs the kernel applies the next layer's activation quantiser (Eq. 1b-1c) and
+// writes the next layer's packed bit planes: a wave's 64 lanes are 64 consecutive channels, so the ballot of level
+// bit j over the wave IS the pair of 32-channel words of plane j; the work-groups also clear the zero ring.
+template <int KW, int KA, int P, int ST, int FS, bool REQ>
 __global__ void __launch_bounds__(256)
 bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
              const float *__restrict__ scale, const float *__restrict__ offset,
-             int32_t *__restrict__ acc_out, float *__restrict__ out_f32, const LaneShape sh)
+             int32_t *__restrict__ acc_out, float *__restrict__ out_f32, uint32_t *__restrict__ packed_next,
+             const LaneShape sh)
 {
     constexpr int NCLS = KW + KA - 1;
     constexpr int NSEG = (P - 1) * ST + FS;       // input positions one filter row of the run touches
@@ -117,6 +126,24 @@ bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
     const unsigned lane = threadIdx.x & 63;
     const unsigned lane4 = lane * 4u;
     const int wave = uni(threadIdx.x >> 6);
+    if constexpr (REQ) {
+        // zero ring of the next layer's tensor, dealt evenly to all work-groups of the grid (also those beyond the
+        // last tile): top row, bottom row, then the left/right columns of every image
+        const int kmax = sh.k_next;
+        const int wpp = sh.cwn * kmax;
+        for (int idx = (int)(blockIdx.x * 256 + threadIdx.x); idx < sh.ring_total; idx += (int)(gridDim.x * 256)) {
+            const int ni = idx / sh.ring_per_image;
+            const int rem = idx - ni * sh.ring_per_image;
+            const int b = rem / wpp;
+            const int word = rem - b * wpp;
+            int hp, wp;
+            if (b < sh.OWn) { hp = 0; wp = b; }
+            else if (b < 2 * sh.OWn) { hp = sh.OHn - 1; wp = b - sh.OWn; }
+            else { const int cc = b - 2 * sh.OWn; hp = 1 + (cc >> 1); wp = (cc & 1) ? sh.OWn - 1 : 0; }
+            const int wd = word / kmax, j = word - wd * kmax;
+            packed_next[((size_t)wd * sh.total_next + ((size_t)ni * sh.OHn + hp) * sh.OWn + wp) * kmax + j] = 0u;
+        }
+    }
     const int wgi = (int)(blockIdx.x & 7) * sh.xcd_chunk + (int)(blockIdx.x >> 3);
     const int tile = wgi * 4 + wave;
     if ((int)(blockIdx.x >> 3) >= sh.xcd_chunk || tile >= sh.ntiles) return;
@@ -264,6 +291,29 @@ bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
         for (int ln = 0; ln < PF_LINES; ++ln) asm volatile("" ::"v"(pf_ahead[ln]));
     }
 
+    if constexpr (REQ) {
+        // ---- Eq. 14, the affine map and the next layer's quantiser; lanes 0 and 32 store the two words of a plane
+        const size_t posn = ((size_t)n * sh.OHn + oh + kActBorder) * sh.OWn + ow0 + kActBorder;
+        const int wd = kg * 2 + (int)(lane >> 5);
+        const bool writer = (lane & 31u) == 0u && wd < sh.cwn;
+        uint32_t *dst = packed_next + ((size_t)wd * sh.total_next + posn) * sh.k_next;
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            uint32_t v = cls[p][0];
+#pragma unroll
+            for (int c = 1; c < NCLS; ++c) v += cls[p][c] << c;
+            const uint32_t lv = k < sh.K ? requant_level((int32_t)v, sc, of, sh.alpha, sh.qs) : 0u;
+#pragma unroll
+            for (int j = 0; j < kMaxBits; ++j) {
+                if (j < sh.k_next) {
+                    const unsigned long long m = __ballot((lv >> j) & 1u);
+                    const uint32_t word = (lane >> 5) ? (uint32_t)(m >> 32) : (uint32_t)m;
+                    if (writer) dst[(size_t)p * sh.k_next + j] = word;
+                }
+            }
+        }
+        return;
+    }
     // ---- Eq. 14 and the affine epilogue; per position a wave writes 64 consecutive values
     if (k < sh.K) {
         int32_t acc[P];
@@ -301,10 +351,10 @@ template <int KW, int KA, int ST, int FS = 3> struct LaneRun {
     static constexpr int SMALL = ST == 1 ? 7 : 4;
 };
 
-template <int KW, int KA, int P, int ST, int FS>
+template <int KW, int KA, int P, int ST, int FS, bool REQ>
 static int launch_lane_cfg(const ConvArgs &a)
 {
-    if (a.wtop || a.next) return EBS_ERR_UNSUPPORTED;
+    if (a.wtop || (a.next != nullptr) != REQ) return EBS_ERR_UNSUPPORTED;
     if (a.R != FS || a.S != FS || a.stride != ST || a.pad > kActBorder || a.OW < P) return EBS_ERR_UNSUPPORTED;
     // the loop takes two steps (filter row, word) per trip; one lane per step touches the step's input piece
     if (((FS * a.cw) & 1) || FS * a.cw > 64) return EBS_ERR_UNSUPPORTED;
@@ -330,6 +380,19 @@ static int launch_lane_cfg(const ConvArgs &a)
     sh.div_runs = make_fastdiv((uint32_t)sh.runs);
     sh.div_oh = make_fastdiv((uint32_t)a.OH);
 
+    if (REQ) {
+        sh.alpha = a.alpha;
+        sh.k_next = a.k_next;
+        sh.qs = requant_qs(a.alpha, a.k_next);
+        sh.OHn = a.OH + 2 * kActBorder;
+        sh.OWn = a.OW + 2 * kActBorder;
+        sh.cwn = words_per_pixel(a.K);
+        sh.total_next = a.N * sh.OHn * sh.OWn;
+        const long long per_image = (2LL * sh.OWn + 2LL * a.OH) * sh.cwn * a.k_next;
+        if (per_image * a.N > (1LL << 30)) return EBS_ERR_UNSUPPORTED;
+        sh.ring_per_image = (int)per_image;
+        sh.ring_total = (int)(per_image * a.N);
+    }
     const DeviceShape *dev = device_shape();
     if (!dev) return EBS_ERR_HIP;
     if (!dev->gfx950) return EBS_ERR_UNSUPPORTED;       // run lengths and die numbering are gfx950's
@@ -338,22 +401,22 @@ static int launch_lane_cfg(const ConvArgs &a)
     // one generation of resident waves of a die: 32 compute units x 4 SIMDs x 8 waves
     sh.touch_ahead_pos = (dev->cus / 8 * 32 + sh.kgroups - 1) / sh.kgroups;
     sh.touch_ahead = sh.touch_ahead_pos * sh.kgroups;
-    hipLaunchKernelGGL((bd_conv_lane<KW, KA, P, ST, FS>), dim3((unsigned)(sh.xcd_chunk * 8)), dim3(256), 0, a.stream,
-                       a.act, a.wgt, a.scale, a.offset, a.acc, a.out, sh);
+    hipLaunchKernelGGL((bd_conv_lane<KW, KA, P, ST, FS, REQ>), dim3((unsigned)(sh.xcd_chunk * 8)), dim3(256), 0, a.stream,
+                       a.act, a.wgt, a.scale, a.offset, a.acc, a.out, a.next, sh);
     return hip_ok(hipGetLastError());
 }
 
 // sel: 0 = large runs, 1 = small runs
-template <int KW, int KA, int FS>
+template <int KW, int KA, int FS, bool REQ>
 static int launch_lane_fs(const ConvArgs &a, int sel)
 {
     if (a.stride == 1) {
-        if (sel == 0) return launch_lane_cfg<KW, KA, LaneRun<KW, KA, 1, FS>::BIG, 1, FS>(a);
-        return launch_lane_cfg<KW, KA, LaneRun<KW, KA, 1, FS>::SMALL, 1, FS>(a);
+        if (sel == 0) return launch_lane_cfg<KW, KA, LaneRun<KW, KA, 1, FS>::BIG, 1, FS, REQ>(a);
+        return launch_lane_cfg<KW, KA, LaneRun<KW, KA, 1, FS>::SMALL, 1, FS, REQ>(a);
     }
     if (a.stride == 2) {
-        if (sel == 0) return launch_lane_cfg<KW, KA, LaneRun<KW, KA, 2, FS>::BIG, 2, FS>(a);
-        return launch_lane_cfg<KW, KA, LaneRun<KW, KA, 2, FS>::SMALL, 2, FS>(a);
+        if (sel == 0) return launch_lane_cfg<KW, KA, LaneRun<KW, KA, 2, FS>::BIG, 2, FS, REQ>(a);
+        return launch_lane_cfg<KW, KA, LaneRun<KW, KA, 2, FS>::SMALL, 2, FS, REQ>(a);
     }
     return EBS_ERR_UNSUPPORTED;
 }
@@ -361,8 +424,13 @@ static int launch_lane_fs(const ConvArgs &a, int sel)
 template <int KW, int KA>
 static int launch_lane_pair_impl(const ConvArgs &a, int sel)
 {
-    if (a.R == 3 && a.S == 3) return launch_lane_fs<KW, KA, 3>(a, sel);
-    if (a.R == 1 && a.S == 1) return launch_lane_fs<KW, KA, 1>(a, sel);
+    if (a.next) {
+        if (a.R == 3 && a.S == 3) return launch_lane_fs<KW, KA, 3, true>(a, sel);
+        if (a.R == 1 && a.S == 1) return launch_lane_fs<KW, KA, 1, true>(a, sel);
+        return EBS_ERR_UNSUPPORTED;
+    }
+    if (a.R == 3 && a.S == 3) return launch_lane_fs<KW, KA, 3, false>(a, sel);
+    if (a.R == 1 && a.S == 1) return launch_lane_fs<KW, KA, 1, false>(a, sel);
     return EBS_ERR_UNSUPPORTED;
 }
 

@@ -96,6 +96,57 @@ static int kt_of(int budget, int kw, int ka)
     return t[kw + ka - 2];
 }
 
+// Whether (and with which run length first) the channel-per-lane kernel should take the layer: -1 = no, else the
+// preferred run selection (0 = large, 1 = small); the other one is the second choice.
+static int lane_choice(const ConvArgs &a)
+{
+    const long long positions = (long long)a.N * a.OH * a.OW;
+    const int rs = a.R * a.S;
+    // Channel-per-lane kernel (3x3 filters): no LDS, scalar position arithmetic, direct 256-byte stores.  It wins
+    // where the per-work-group costs of the tiled kernel weigh most - few plane pairs (short kernels), short
+    // reductions - and loses on the deepest stride-1 layer (few positions: too few tiles), at the highest
+    // bitwidths of the layers with many positions, and when many of a wave's 64 channel lanes would idle.
+    // Measured on the ResNet-18 shapes, all 16 pairs, both kernels forced in turn.
+    if (rs == 9 && a.R == 3 && a.kw <= 4 && a.ka <= 4 && !a.wtop && (a.cw & 1) == 0 && (a.K % 64 == 0 || a.K >= 256)) {
+        const int pairs = a.kw * a.ka;
+        bool use = false;
+        if (positions >= 8192) {
+            if (a.stride == 1)
+                use = pairs <= 4 || (pairs <= 9 && !(a.ka == 4 && a.kw >= 3)) || positions < 16384;
+            else
+                use = pairs <= 8;
+        } else if (positions >= 3072 && a.stride == 2) {
+            use = pairs <= 6;
+        }
+        if (use) {
+            // small runs where the large ones leave fewer than six tiles per SIMD and divide the row
+            const int big = lane_run_length(a.kw, a.ka, a.stride, a.R, 0), small = lane_run_length(a.kw, a.ka, a.stride, a.R, 1);
+            int sel = 0;
+            if (big > 0 && small > 0 && a.OW >= big) {
+                const long long tiles_big = (long long)a.N * a.OH * ((a.OW + big - 1) / big) * ((a.K + 63) / 64);
+                if (tiles_big < 6 * 1024 && small < big && a.OW % small == 0) sel = 1;
+            } else {
+                sel = 1;
+            }
+            // the last run of a row is moved left and recomputes the overlap: not where that is over 15 % of the work
+            const int run = sel ? small : big;
+            if (run > 0 && (long long)((a.OW + run - 1) / run) * run * 100 <= (long long)a.OW * 115) {
+                return sel;
+            }
+        }
+    }
+    // 1x1 filters: the same kernel with the short runs (the long ones were slower on every shape tried) wherever
+    // the reduction has at least eight words, and at nine plane pairs on shorter ones; layers with a short
+    // reduction and fewer pairs are bound by their output writes and do as well or better with the wide tiles.
+    // Measured on the ResNet-50 bottleneck shapes at (2,4), (3,3), (4,2): -3..-10 % (256->64 @56x56), -10 %
+    // (1024->256 @14x14), -7..-10 % (256->1024 @14x14), -17 % (64->256 @56x56 at (3,3)).
+    if (rs == 1 && a.kw <= 4 && a.ka <= 4 && !a.wtop && positions >= 8192 && (a.cw & 1) == 0 && a.K % 64 == 0 &&
+        (a.cw >= 8 || a.kw * a.ka >= 8)) {
+        return 1;
+    }
+    return -1;
+}
+
 // Fused re-quantisation: the K4 kernels whose work-groups own whole 32-channel words; layers with few
 // positions and a long reduction split the reduction among the waves instead (work-groups of 8 channels).
 int launch_requant_tiled(const ConvArgs &a)
@@ -106,6 +157,15 @@ int launch_requant_tiled(const ConvArgs &a)
     {
         const int rc = launch_conv_pair(a);
         if (rc != EBS_ERR_UNSUPPORTED) return rc;
+    }
+    // the channel-per-lane kernel where the plain convolution would use it (unsigned weights only)
+    if (!a.wtop) {
+        const int sel = lane_choice(a);
+        if (sel >= 0) {
+            int rc = launch_conv_lane(a, sel);
+            if (rc == EBS_ERR_UNSUPPORTED) rc = launch_conv_lane(a, 1 - sel);
+            if (rc != EBS_ERR_UNSUPPORTED) return rc;
+        }
     }
     int order[4];
     int n = 0;
@@ -136,49 +196,12 @@ int launch_conv_tiled(const ConvArgs &a, int variant)
     // 3x3 layers with at most 16 input channels: two taps per word (half the AND + bitcount work of the
     // one-tap-per-word kernels, whose words are half zeros there)
     if (a.C <= 16 && rs == 9 && a.R == 3 && a.K <= 32) order[n++] = V_PAIR;
-    // Channel-per-lane kernel (3x3 filters): no LDS, scalar position arithmetic, direct 256-byte stores.  It wins
-    // where the per-work-group costs of the tiled kernel weigh most - few plane pairs (short kernels), short
-    // reductions - and loses on the deepest stride-1 layer (few positions: too few tiles), at the highest
-    // bitwidths of the layers with many positions, and when many of a wave's 64 channel lanes would idle.
-    // Measured on the ResNet-18 shapes, all 16 pairs, both kernels forced in turn.
-    if (rs == 9 && a.R == 3 && a.kw <= 4 && a.ka <= 4 && !a.wtop && (a.cw & 1) == 0 && (a.K % 64 == 0 || a.K >= 256)) {
-        const int pairs = a.kw * a.ka;
-        bool use = false;
-        if (positions >= 8192) {
-            if (a.stride == 1)
-                use = pairs <= 4 || (pairs <= 9 && !(a.ka == 4 && a.kw >= 3)) || positions < 16384;
-            else
-                use = pairs <= 8;
-        } else if (positions >= 3072 && a.stride == 2) {
-            use = pairs <= 6;
+    {
+        const int sel = lane_choice(a);
+        if (sel >= 0) {
+            order[n++] = V_LANE + sel;
+            order[n++] = V_LANE + 1 - sel;
         }
-        if (use) {
-            // small runs where the large ones leave fewer than six tiles per SIMD and divide the row
-            const int big = lane_run_length(a.kw, a.ka, a.stride, a.R, 0), small = lane_run_length(a.kw, a.ka, a.stride, a.R, 1);
-            int sel = 0;
-            if (big > 0 && small > 0 && a.OW >= big) {
-                const long long tiles_big = (long long)a.N * a.OH * ((a.OW + big - 1) / big) * ((a.K + 63) / 64);
-                if (tiles_big < 6 * 1024 && small < big && a.OW % small == 0) sel = 1;
-            } else {
-                sel = 1;
-            }
-            // the last run of a row is moved left and recomputes the overlap: not where that is over 15 % of the work
-            const int run = sel ? small : big;
-            if (run > 0 && (long long)((a.OW + run - 1) / run) * run * 100 <= (long long)a.OW * 115) {
-                order[n++] = V_LANE + sel;
-                order[n++] = V_LANE + 1 - sel;
-            }
-        }
-    }
-    // 1x1 filters: the same kernel with the short runs (the long ones were slower on every shape tried) wherever
-    // the reduction has at least eight words, and at nine plane pairs on shorter ones; layers with a short
-    // reduction and fewer pairs are bound by their output writes and do as well or better with the wide tiles.
-    // Measured on the ResNet-50 bottleneck shapes at (2,4), (3,3), (4,2): -3..-10 % (256->64 @56x56), -10 %
-    // (1024->256 @14x14), -7..-10 % (256->1024 @14x14), -17 % (64->256 @56x56 at (3,3)).
-    if (rs == 1 && a.kw <= 4 && a.ka <= 4 && !a.wtop && positions >= 8192 && (a.cw & 1) == 0 && a.K % 64 == 0 &&
-        (a.cw >= 8 || a.kw * a.ka >= 8)) {
-        order[n++] = V_LANE + 1;
-        order[n++] = V_LANE;
     }
     // reduction split: 8 channels per wave for one-bit weights with 3-4 bit activations (4 would leave too
     // little arithmetic per step), else the 16-register tiles

@@ -51,6 +51,9 @@ GEOS = [  # N, C, H, W, K, R, S, stride, pad
     (3, 16, 12, 10, 16, 3, 3, 1, 1),      # 16 input channels: the two-taps-per-word kernel, 16 channel lanes
     (2, 16, 14, 14, 32, 3, 3, 2, 1),      # the same at stride 2 with 32 channel lanes
     (2, 9, 7, 9, 21, 3, 3, 1, 0),         # fewer channels, K ragged, no padding
+    (8, 64, 40, 28, 260, 3, 3, 1, 1),     # 8960 positions: the channel-per-lane kernel (unsigned weights), K ragged vs 64 and 32
+    (16, 64, 48, 56, 128, 3, 3, 2, 1),    # the same at stride 2
+    (8, 256, 34, 32, 64, 1, 1, 1, 0),     # 1x1 with eight reduction words: lane kernel too
 ]
 
 
