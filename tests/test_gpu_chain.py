@@ -109,3 +109,53 @@ def test_chain_as_captured_graph_replays_identically(oracle_mod):
         torch.cuda.synchronize()
         for i, (t, want) in enumerate(zip(g.packed, eager)):
             assert torch.equal(t, want), f"replay {rep}: packed tensor {i} differs from the eager run"
+
+
+def test_plain_convolutions_as_captured_graph(oracle_mod):
+    """ebs_pack_activations + ebs_mixed_conv2d of three layers, one per convolution kernel (channel-per-lane,
+    two-taps-per-word, tiled), captured once and replayed with eager work in between: every replay must equal the
+    eager result, which must equal the oracle."""
+    import torch
+    from gpu_harness import upload
+    shapes = [  # N, C, H, W, K, R, S, stride, pad, k_w, k_a
+        (8, 64, 40, 28, 64, 3, 3, 1, 1, 2, 2),      # 8960 positions: channel-per-lane kernel
+        (4, 16, 12, 12, 16, 3, 3, 1, 1, 3, 3),      # 16 input channels: two taps per word
+        (2, 128, 10, 10, 40, 3, 3, 1, 1, 4, 4),     # tiled kernel
+    ]
+    cases = []
+    for i, (N, C, H, W, K, R, S, st, pad, kw, ka) in enumerate(shapes):
+        inp = wl.random_case(31000 + i, N, C, H, W, K, R, S, st, pad, kw, ka, per_channel=True, with_offset=True)
+        cases.append((inp, upload(inp, kw, ka, st, pad), st, pad, kw, ka))
+
+    def run(stream=None):
+        for inp, d, st, pad, kw, ka in cases:
+            g = d["g"]
+            ebs.ebs_pack_activations(d["a"], g["N"], g["H"], g["W"], g["C"], ka, d["pa"], stream)
+            ebs.ebs_mixed_conv2d(d["pa"], d["pw"], g["N"], g["C"], g["H"], g["W"], g["K"], g["R"], g["S"], st, pad, kw, ka,
+                                 d["scale"], d["offset"], d["per_channel"], d["acc"], d["out"], stream)
+
+    for inp, d, st, pad, kw, ka in cases:
+        g = d["g"]
+        ebs.ebs_pack_weights(d["q"], g["K"], g["C"], g["R"], g["S"], kw, d["pw"])
+    run()
+    torch.cuda.synchronize()
+    eager = []
+    for inp, d, st, pad, kw, ka in cases:
+        assert np.array_equal(d["acc"].cpu().numpy(), oracle_mod.conv2d_levels(inp["a"], inp["q"], st, pad))
+        eager.append((d["acc"].clone(), d["out"].clone()))
+
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.graph(graph, stream=side):
+        run(torch.cuda.current_stream())
+    for rep in range(3):
+        for inp, d, st, pad, kw, ka in cases:
+            d["acc"].fill_(POISON)                 # eager work between the replays
+            d["out"].fill_(0.0)
+            d["pa"].fill_(POISON)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for (inp, d, st, pad, kw, ka), (acc, out) in zip(cases, eager):
+            assert torch.equal(d["acc"], acc) and torch.equal(d["out"], out), f"replay {rep} differs from the eager run"
