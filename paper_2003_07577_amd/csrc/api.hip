@@ -108,7 +108,7 @@ using namespace ebs;
 
 extern "C" {
 
-int ebs_version(void) { return 210; }
+int ebs_version(void) { return 211; }
 
 const char *ebs_last_hip_error(void) { return hipGetErrorName(ebs::last_hip_error()); }
 

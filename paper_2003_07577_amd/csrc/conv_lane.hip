@@ -15,6 +15,7 @@ EBS_LANE_PAIRS(EBS_DECL)
 // sel: 0 = large runs of positions, 1 = small runs.
 // EBS_ERR_UNSUPPORTED for anything but 3x3 (pad <= 1) and 1x1 filters, stride 1 or 2, bitwidths up to 4, an even
 // number of (filter row, 32-channel word) steps up to 64, unsigned weights, and output rows at least one run long.
+// 1x1 layers with one output position per image (fully-connected layers) run over 8 (sel 0) or 4 images instead.
 int launch_conv_lane(const ConvArgs &a, int sel)
 {
 #define EBS_CASE(kw, ka) case (kw) * 8 + (ka): return launch_lane_pair<kw, ka>(a, sel);

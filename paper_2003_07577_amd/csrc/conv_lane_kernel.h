@@ -17,6 +17,12 @@
 //  * a reduction step is (filter row r, word w); the operands of the next step are requested
 //    before the current step is multiplied.  The loop body is one block of instructions (offsets
 //    advance by selects, not branches), which keeps the requests where they are written.
+//  * layers whose output is one position per image (a fully-connected layer as a 1x1 convolution) take runs of
+//    P consecutive IMAGES instead (template stride 0): the input piece of a step is then P pieces of k_a words,
+//    one per image, and the launcher describes the batch as one output row of N positions.  Such layers have few
+//    positions and a long reduction, so there the four waves of a work-group share ONE tile and take a quarter
+//    of the reduction words each; the partial sums meet in LDS (the only use of LDS and of a barrier here) and
+//    each wave finishes and stores its share of the positions.
 #pragma once
 #include "ebs_internal.h"
 #include "fastdiv.h"
@@ -117,7 +123,10 @@ bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
              const LaneShape sh)
 {
     constexpr int NCLS = KW + KA - 1;
-    constexpr int NSEG = (P - 1) * ST + FS;       // input positions one filter row of the run touches
+    constexpr bool IMG = ST == 0;                 // runs over images (1x1 filter, one output position per image)
+    static_assert(!IMG || (FS == 1 && !REQ), "image runs: 1x1 filters, plain outputs");
+    constexpr int XST = IMG ? 1 : ST;             // distance of consecutive positions in a step's registers
+    constexpr int NSEG = (P - 1) * XST + FS;      // input positions one filter row of the run touches
     constexpr int XN = NSEG * KA;                 // dwords of one step's input piece
     constexpr int QSTEP = kWgtGroup * KW;         // weights [k/16][tap][word][k%16][plane]: dwords per (tap, word)
 
@@ -145,7 +154,7 @@ bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
         }
     }
     const int wgi = (int)(blockIdx.x & 7) * sh.xcd_chunk + (int)(blockIdx.x >> 3);
-    const int tile = wgi * 4 + wave;
+    const int tile = IMG ? wgi : wgi * 4 + wave;  // image runs: the work-group's waves split the tile's reduction
     if ((int)(blockIdx.x >> 3) >= sh.xcd_chunk || tile >= sh.ntiles) return;
     const int ptile = (int)fd_div((uint32_t)tile, sh.div_kgroups);
     const int kg = tile - ptile * sh.kgroups;
@@ -166,9 +175,16 @@ bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
     const float of = offset ? offset[ci] : 0.0f;
 
     // ---- the reduction: steps (filter row r, word w), w fastest.  Offsets of a step's operands (dwords):
-    unsigned x_off = (unsigned)uni((n * sh.plane_pos + (oh * ST + sh.origin) * sh.Wp + ow0 * ST + sh.origin) * KA);
-    unsigned q_off = 0;
+    // (image runs: "ow0" is the first image of the run, its one input position is the piece)
+    auto piece_of = [&](int n_, int oh_, int ow_) {
+        if constexpr (IMG) return (unsigned)uni((ow_ * sh.plane_pos + sh.origin * sh.Wp + sh.origin) * KA);
+        else return (unsigned)uni((n_ * sh.plane_pos + (oh_ * ST + sh.origin) * sh.Wp + ow_ * ST + sh.origin) * KA);
+    };
+    const unsigned img_step = (unsigned)sh.plane_pos * KA;      // image runs: dwords from one image's piece to the next
     const unsigned x_wstep = (unsigned)sh.total_pos * KA;                       // next word
+    const int my_steps = IMG ? sh.cw >> 2 : FS * sh.cw;                         // reduction steps of this wave
+    unsigned x_off = piece_of(n, oh, ow0) + (IMG ? (unsigned)(wave * my_steps) * x_wstep : 0u);
+    unsigned q_off = IMG ? (unsigned)(wave * my_steps * QSTEP) : 0u;
     const unsigned x_rwrap = (unsigned)sh.Wp * KA - (unsigned)(sh.cw - 1) * x_wstep;   // first word of the next filter row
     const unsigned q_rwrap = (unsigned)((FS - 1) * sh.cw * QSTEP + QSTEP);
     const unsigned q_tap = (unsigned)(sh.cw * QSTEP);
@@ -179,24 +195,25 @@ bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
     //  * the first tiles of a die (nothing ran before them) touch their own pieces,
     //  * every tile touches the pieces of the tile that the die starts `touch_ahead` tiles later - about one
     //    generation of resident waves - so that tile finds them in the L2 when it starts.
-    constexpr int PF_LINES = (XN - 1 + 31) / 32 + 1;
+    constexpr int PF_LINES = IMG ? P : (XN - 1 + 31) / 32 + 1;
     const __amdgpu_buffer_rsrc_t abuf = raw_buffer(act, sh.act_bytes);
     auto touch = [&](unsigned piece0, uint32_t (&pf)[PF_LINES]) {
-        const int steps = FS * sh.cw;             // <= 64 (launcher)
+        const int steps = my_steps;               // <= 64 (launcher)
         const int sl = (int)lane < steps ? (int)lane : steps - 1;
         const int r = (sl >= sh.cw) + (sl >= 2 * sh.cw);
         const unsigned piece = piece0 + (unsigned)(sl - r * sh.cw) * x_wstep + (unsigned)(r * sh.Wp * KA);
 #pragma unroll
         for (int ln = 0; ln < PF_LINES; ++ln) {
-            const int e = ln * 32 < XN - 1 ? ln * 32 : XN - 1;
-            pf[ln] = __builtin_amdgcn_raw_buffer_load_b32(abuf, (int)((piece + (unsigned)e) * 4u), 0, 0);
+            const unsigned e = IMG ? (unsigned)ln * img_step : (unsigned)(ln * 32 < XN - 1 ? ln * 32 : XN - 1);
+            pf[ln] = __builtin_amdgcn_raw_buffer_load_b32(abuf, (int)((piece + e) * 4u), 0, 0);
         }
     };
     uint32_t pf_own[PF_LINES], pf_ahead[PF_LINES];
     const int die_tile = (int)(blockIdx.x >> 3) * 4 + wave;           // index among the die's tiles
-    const bool touch_own = die_tile < sh.touch_ahead && FS * sh.cw > 2;   // (two steps are requested at once anyway)
+    // (image runs: small grids, every wave is among the first of its die)
+    const bool touch_own = IMG || (die_tile < sh.touch_ahead && FS * sh.cw > 2);  // (two steps are requested at once anyway)
     if (touch_own) touch(x_off, pf_own);
-    const bool touch_next = kg == 0 && die_tile + sh.touch_ahead < sh.xcd_chunk * 4 && tile + sh.touch_ahead < sh.ntiles;
+    const bool touch_next = !IMG && kg == 0 && die_tile + sh.touch_ahead < sh.xcd_chunk * 4 && tile + sh.touch_ahead < sh.ntiles;
     if (touch_next) {
         // touch_ahead is a multiple of the channel groups: the tile ahead is channel group 0 of its positions
         const int ptile_a = ptile + sh.touch_ahead_pos;
@@ -206,17 +223,24 @@ bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
         const int oh_a = grow_a - n_a * sh.OH;
         int ow_a = run_a * P;
         if (ow_a > sh.OW - P) ow_a = sh.OW - P;
-        touch((unsigned)uni((n_a * sh.plane_pos + (oh_a * ST + sh.origin) * sh.Wp + ow_a * ST + sh.origin) * KA), pf_ahead);
+        touch(piece_of(n_a, oh_a, ow_a), pf_ahead);
     }
     int w_next = 0;                               // word index of the step the offsets point at
-    int left = FS * sh.cw;                        // steps not yet requested
+    int left = my_steps;                          // steps not yet requested
     // request the operands of the step the offsets point at (one scalar piece of input, one per-lane load per
     // tap that brings the k_w planes), then move the offsets one step on - without a branch, so that the loop
     // body stays one block of instructions; past the last step the offsets stay where they are
     auto issue = [&](uint32_t (&x)[XN], uint32_t (&q)[FS][KW]) {
         const uint32_t *xs = act + x_off;         // wave-uniform address: scalar loads
+        if constexpr (IMG) {
 #pragma unroll
-        for (int e = 0; e < XN; ++e) x[e] = xs[e];
+            for (int p = 0; p < P; ++p)
+#pragma unroll
+                for (int j = 0; j < KA; ++j) x[p * KA + j] = xs[(unsigned)p * img_step + (unsigned)j];
+        } else {
+#pragma unroll
+            for (int e = 0; e < XN; ++e) x[e] = xs[e];
+        }
 #pragma unroll
         for (int s = 0; s < FS; ++s) BufferLoad<KW>::run(q[s], wbuf, qlane, (q_off + (unsigned)s * q_tap) * 4u);
         const bool more = --left > 0;
@@ -239,7 +263,7 @@ bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
                 for (int i = 0; i < KW; ++i)
 #pragma unroll
                     for (int j = 0; j < KA; ++j) {
-                        const uint32_t v = q[s][i] & x[(p * ST + s) * KA + j];
+                        const uint32_t v = q[s][i] & x[(p * XST + s) * KA + j];
                         if (FIRST && s == 0 && (i == 0 || j == KA - 1))
                             cls[p][i + j] = lane_bcnt_first(v);
                         else
@@ -255,7 +279,7 @@ bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
     // (requested one step ago), then requests the next step's, then multiplies: the wait the multiplication needs
     // would otherwise also cover the request just made.
     uint32_t xa[XN], xb[XN], qa[FS][KW], qb[FS][KW];
-    const int trips = (FS * sh.cw) >> 1;
+    const int trips = my_steps >> 1;
     issue(xa, qa);
     __builtin_amdgcn_s_waitcnt(0xC07F);           // lgkmcnt(0)
     __builtin_amdgcn_sched_barrier(0);
@@ -314,6 +338,36 @@ bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
         }
         return;
     }
+    if constexpr (IMG) {
+        // ---- Eq. 14 over the wave's quarter of the reduction; the quarters meet in LDS, and wave w finishes
+        //      positions w, w + 4, ... (sum of the four quarters, affine epilogue, 64 consecutive values each)
+        __shared__ uint32_t part[4][P][64];
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            uint32_t v = 0;
+#pragma unroll
+            for (int c = 0; c < NCLS; ++c) v += cls[p][c] << c;
+            part[wave][p][lane] = v;
+        }
+        __syncthreads();
+        const size_t o0 = (size_t)ow0 * sh.K + (size_t)(kg * 64);
+        const unsigned prow = (unsigned)sh.K * 4u;
+        const unsigned span = (unsigned)(P - 1) * prow + (unsigned)(sh.K - kg * 64 < 64 ? sh.K - kg * 64 : 64) * 4u;
+        const __amdgpu_buffer_rsrc_t ibuf = raw_buffer(acc_out + o0, span);
+        const __amdgpu_buffer_rsrc_t fbuf = raw_buffer(out_f32 ? out_f32 + o0 : nullptr, out_f32 ? span : 0u);
+        if (k < sh.K) {
+#pragma unroll
+            for (int pp = 0; pp < P / 4; ++pp) {
+                const int p = wave + 4 * pp;
+                const uint32_t v = part[0][p][lane] + part[1][p][lane] + part[2][p][lane] + part[3][p][lane];
+                __builtin_amdgcn_raw_buffer_store_b32(v, ibuf, (int)lane4, (int)((unsigned)p * prow), 0);
+                if (out_f32)
+                    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, fmaf((float)(int32_t)v, sc, of)),
+                                                          fbuf, (int)lane4, (int)((unsigned)p * prow), 0);
+            }
+        }
+        return;
+    }
     // ---- Eq. 14 and the affine epilogue; per position a wave writes 64 consecutive values
     if (k < sh.K) {
         int32_t acc[P];
@@ -354,20 +408,27 @@ template <int KW, int KA, int ST, int FS = 3> struct LaneRun {
 template <int KW, int KA, int P, int ST, int FS, bool REQ>
 static int launch_lane_cfg(const ConvArgs &a)
 {
+    constexpr bool IMG = ST == 0;       // runs over images: one output position per image
     if (a.wtop || (a.next != nullptr) != REQ) return EBS_ERR_UNSUPPORTED;
-    if (a.R != FS || a.S != FS || a.stride != ST || a.pad > kActBorder || a.OW < P) return EBS_ERR_UNSUPPORTED;
+    if (a.R != FS || a.S != FS || a.pad > kActBorder) return EBS_ERR_UNSUPPORTED;
+    if (IMG ? (a.OH != 1 || a.OW != 1 || a.N < P) : (a.stride != ST || a.OW < P)) return EBS_ERR_UNSUPPORTED;
+    static_assert(!IMG || P % 4 == 0, "image runs: each of the four waves finishes P / 4 positions");
+    // image runs: the batch is described to the kernel as one output row of N positions
+    const int rows = IMG ? 1 : a.N * a.OH;
+    const int row_len = IMG ? a.N : a.OW;
     // the loop takes two steps (filter row, word) per trip; one lane per step touches the step's input piece
-    if (((FS * a.cw) & 1) || FS * a.cw > 64) return EBS_ERR_UNSUPPORTED;
+    // (image runs: per wave, a quarter of the words)
+    if (IMG ? ((a.cw & 7) || a.cw > 256) : (((FS * a.cw) & 1) || FS * a.cw > 64)) return EBS_ERR_UNSUPPORTED;
     constexpr int FSZ = FS * FS;
     LaneShape sh{};
-    sh.K = a.K; sh.cw = a.cw; sh.OH = a.OH; sh.OW = a.OW;
+    sh.K = a.K; sh.cw = a.cw; sh.OH = IMG ? 1 : a.OH; sh.OW = row_len;
     sh.Wp = a.W + 2 * kActBorder;
     sh.plane_pos = (a.H + 2 * kActBorder) * sh.Wp;
     sh.total_pos = a.N * sh.plane_pos;
     sh.origin = kActBorder - a.pad;
-    sh.runs = (a.OW + P - 1) / P;
+    sh.runs = (row_len + P - 1) / P;
     sh.kgroups = (a.K + 63) / 64;
-    long long ntiles = (long long)a.N * a.OH * sh.runs * sh.kgroups;
+    long long ntiles = (long long)rows * sh.runs * sh.kgroups;
     if (ntiles > (1LL << 30)) return EBS_ERR_UNSUPPORTED;
     sh.ntiles = (int)ntiles;
     sh.per_channel = a.per_channel;
@@ -378,7 +439,7 @@ static int launch_lane_cfg(const ConvArgs &a)
     sh.wgt_bytes = (unsigned)wgt_bytes;
     sh.div_kgroups = make_fastdiv((uint32_t)sh.kgroups);
     sh.div_runs = make_fastdiv((uint32_t)sh.runs);
-    sh.div_oh = make_fastdiv((uint32_t)a.OH);
+    sh.div_oh = make_fastdiv((uint32_t)sh.OH);
 
     if (REQ) {
         sh.alpha = a.alpha;
@@ -396,7 +457,7 @@ static int launch_lane_cfg(const ConvArgs &a)
     const DeviceShape *dev = device_shape();
     if (!dev) return EBS_ERR_HIP;
     if (!dev->gfx950) return EBS_ERR_UNSUPPORTED;       // run lengths and die numbering are gfx950's
-    const long long wgs = (ntiles + 3) / 4;
+    const long long wgs = IMG ? ntiles : (ntiles + 3) / 4;
     sh.xcd_chunk = (int)((wgs + 7) / 8);
     // one generation of resident waves of a die: 32 compute units x 4 SIMDs x 8 waves
     sh.touch_ahead_pos = (dev->cus / 8 * 32 + sh.kgroups - 1) / sh.kgroups;
@@ -421,9 +482,18 @@ static int launch_lane_fs(const ConvArgs &a, int sel)
     return EBS_ERR_UNSUPPORTED;
 }
 
+// Runs of images for layers with one output position per image (1x1 filters): 8 images, or 4 for small batches
+template <int KW, int KA>
+static int launch_lane_images(const ConvArgs &a, int sel)
+{
+    if (sel == 0) return launch_lane_cfg<KW, KA, 8, 0, 1, false>(a);
+    return launch_lane_cfg<KW, KA, 4, 0, 1, false>(a);
+}
+
 template <int KW, int KA>
 static int launch_lane_pair_impl(const ConvArgs &a, int sel)
 {
+    if (!a.next && a.R == 1 && a.S == 1 && a.OH == 1 && a.OW == 1) return launch_lane_images<KW, KA>(a, sel);
     if (a.next) {
         if (a.R == 3 && a.S == 3) return launch_lane_fs<KW, KA, 3, true>(a, sel);
         if (a.R == 1 && a.S == 1) return launch_lane_fs<KW, KA, 1, true>(a, sel);

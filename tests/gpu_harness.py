@@ -27,6 +27,7 @@ VARIANT_GEOS = [  # N, C, H, W, K, R, S, stride, pad
     (3, 16, 12, 10, 16, 3, 3, 1, 1),      # 16 input channels: two taps per word; several tiles, an image boundary inside one
     (2, 12, 9, 11, 20, 3, 3, 2, 1),       # fewer than 16 input channels, stride 2, K ragged against the 32 channel lanes
     (1, 7, 6, 5, 3, 3, 3, 1, 0),          # no padding, a single partial tile
+    (301, 256, 1, 1, 200, 1, 1, 1, 0),    # fully-connected: one position per image, batch and K ragged
 ]
 MUST_ACCEPT = [
     {"p4.tile32.ch2", "k4.tile16.ch2", "k4.tile16.ch1", "k4.tile32.ch2"},
@@ -40,11 +41,12 @@ MUST_ACCEPT = [
     {"pair", "p4.tile32.ch1"},
     {"pair", "p4.tile32.ch1"},
     {"pair", "p4.tile32.ch1"},
+    {"p4.tile32.ch4", "k4.tile16.ch4"},
 ]
 # the channel-per-lane kernel (3x3 and 1x1 filters, bitwidths up to four, an even number of reduction steps):
 # shapes whose rows hold a short run
 MUST_ACCEPT_LANE = [{"lane.small"}, {"lane.small"}, set(), set(), {"lane.small"}, set(), {"lane.small"}, {"lane.small"},
-                    set(), set(), set()]
+                    set(), set(), set(), {"lane.big", "lane.small"}]
 
 
 def unpack_weight_pairs(words, K, C, k_w):

@@ -143,3 +143,46 @@ def test_random_shapes_forced_lane_and_pair_kernels(oracle_mod, block):
             assert np.array_equal(d["acc"].cpu().numpy(), ref), (tag, name)
             assert_f32_close(d["out"].cpu().numpy(), fref, ref, inp["scale"], inp["per_channel"])
     assert ran["pair"] + ran["lane.big"] + ran["lane.small"] >= 6, ran
+
+
+@pytest.mark.parametrize("block", range(2))
+def test_random_fully_connected_shapes_forced_image_runs(oracle_mod, block):
+    """Layers with one output position per image (fully-connected layers as 1x1 convolutions; also 2x2 images at
+    stride 2) through the channel-per-lane kernel's runs over images, forced by variant: random batch sizes
+    (ragged against the runs of 8 and 4 images), channel counts ragged against the 64 lanes, 8 to 256 reduction
+    words (the four waves of a work-group take a quarter each)."""
+    import torch
+    names = {ebs.ebs_conv_variant_name(v): v for v in range(ebs.ebs_conv_variant_count() + 1)}
+    rng = np.random.default_rng(7171 + block)
+    ran = {"lane.big": 0, "lane.small": 0}
+    for i in range(8):
+        C = (2048, 8192)[i] if i < 2 else 256 * int(rng.integers(1, 5))      # 8192: the most words a wave's quarter takes
+        N = int(rng.integers(4, 40)) if i < 2 else int(rng.integers(4, 600))
+        K = int(rng.integers(1, 300))
+        hw, st = (2, 2) if i % 4 == 3 else (1, 1)
+        kw, ka = int(rng.integers(1, 5)), int(rng.integers(1, 5))
+        inp = wl.random_case(int(rng.integers(1 << 30)), N, C, hw, hw, K, 1, 1, st, 0, kw, ka,
+                             per_channel=bool(rng.integers(0, 2)), with_offset=bool(rng.integers(0, 2)))
+        tag = f"block{block}.{i} N{N} C{C} HW{hw} K{K} s{st} w{kw} a{ka}"
+        d = upload(inp, kw, ka, st, 0)
+        pack(d)
+        g = d["g"]
+        ref = oracle_mod.conv2d_levels(inp["a"], inp["q"], st, 0)
+        assert ref.shape[1:3] == (1, 1)
+        fref = oracle_mod.dequant(ref, inp["scale"], inp["offset"], inp["per_channel"])
+        for name in ("lane.big", "lane.small"):
+            print(f"[case] {tag} {name}", flush=True)
+            d["acc"].fill_(POISON)
+            d["out"].fill_(float("nan"))
+            rc = ebs.ebs_mixed_conv2d_variant(names[name], d["pa"], d["pw"], g["N"], g["C"], g["H"], g["W"], g["K"], 1, 1,
+                                              st, 0, kw, ka, d["scale"], d["offset"], d["per_channel"], d["acc"],
+                                              d["out"], check=False)
+            if rc == -5:
+                assert N < (8 if name == "lane.big" else 4), (tag, name)      # a batch shorter than one run
+                continue
+            assert rc == 0, (tag, name, rc)
+            torch.cuda.synchronize()
+            ran[name] += 1
+            assert np.array_equal(d["acc"].cpu().numpy(), ref), (tag, name)
+            assert_f32_close(d["out"].cpu().numpy(), fref, ref, inp["scale"], inp["per_channel"])
+    assert ran["lane.big"] >= 6 and ran["lane.small"] >= 6, ran
