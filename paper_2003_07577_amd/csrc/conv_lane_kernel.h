@@ -19,10 +19,10 @@
 //    advance by selects, not branches), which keeps the requests where they are written.
 //  * layers whose output is one position per image (a fully-connected layer as a 1x1 convolution) take runs of
 //    P consecutive IMAGES instead (template stride 0): the input piece of a step is then P pieces of k_a words,
-//    one per image, and the launcher describes the batch as one output row of N positions.  Such layers have few
-//    positions and a long reduction, so there the four waves of a work-group share ONE tile and take a quarter
-//    of the reduction words each; the partial sums meet in LDS (the only use of LDS and of a barrier here) and
-//    each wave finishes and stores its share of the positions.
+//    one per image, and the launcher describes the batch as one output row of N positions.
+//  * SPLIT, for layers with few positions and a long reduction (always with image runs): the four waves of a
+//    work-group share ONE tile and take a quarter of the reduction steps each; the partial sums meet in LDS
+//    (the only use of LDS and of a barrier here) and each wave finishes and stores its share of the positions.
 #pragma once
 #include "ebs_internal.h"
 #include "fastdiv.h"
@@ -115,7 +115,7 @@ template <> struct BufferLoad<4> {
 // REQ: instead of the int32 / fp32 outputs the kernel applies the next layer's activation quantiser (Eq. 1b-1c) and
 // writes the next layer's packed bit planes: a wave's 64 lanes are 64 consecutive channels, so the ballot of level
 // bit j over the wave IS the pair of 32-channel words of plane j; the work-groups also clear the zero ring.
-template <int KW, int KA, int P, int ST, int FS, bool REQ>
+template <int KW, int KA, int P, int ST, int FS, bool REQ, bool SPLIT = false>
 __global__ void __launch_bounds__(256)
 bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
              const float *__restrict__ scale, const float *__restrict__ offset,
@@ -124,7 +124,8 @@ bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
 {
     constexpr int NCLS = KW + KA - 1;
     constexpr bool IMG = ST == 0;                 // runs over images (1x1 filter, one output position per image)
-    static_assert(!IMG || (FS == 1 && !REQ), "image runs: 1x1 filters, plain outputs");
+    static_assert(!IMG || (FS == 1 && SPLIT), "image runs: 1x1 filters, split reduction");
+    static_assert(!SPLIT || !REQ, "split reduction: plain outputs");
     constexpr int XST = IMG ? 1 : ST;             // distance of consecutive positions in a step's registers
     constexpr int NSEG = (P - 1) * XST + FS;      // input positions one filter row of the run touches
     constexpr int XN = NSEG * KA;                 // dwords of one step's input piece
@@ -154,7 +155,7 @@ bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
         }
     }
     const int wgi = (int)(blockIdx.x & 7) * sh.xcd_chunk + (int)(blockIdx.x >> 3);
-    const int tile = IMG ? wgi : wgi * 4 + wave;  // image runs: the work-group's waves split the tile's reduction
+    const int tile = SPLIT ? wgi : wgi * 4 + wave;
     if ((int)(blockIdx.x >> 3) >= sh.xcd_chunk || tile >= sh.ntiles) return;
     const int ptile = (int)fd_div((uint32_t)tile, sh.div_kgroups);
     const int kg = tile - ptile * sh.kgroups;
@@ -182,9 +183,14 @@ bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
     };
     const unsigned img_step = (unsigned)sh.plane_pos * KA;      // image runs: dwords from one image's piece to the next
     const unsigned x_wstep = (unsigned)sh.total_pos * KA;                       // next word
-    const int my_steps = IMG ? sh.cw >> 2 : FS * sh.cw;                         // reduction steps of this wave
-    unsigned x_off = piece_of(n, oh, ow0) + (IMG ? (unsigned)(wave * my_steps) * x_wstep : 0u);
-    unsigned q_off = IMG ? (unsigned)(wave * my_steps * QSTEP) : 0u;
+    // reduction steps of this wave, and the (filter row, word) of its first one
+    const int my_steps = SPLIT ? (FS * sh.cw) >> 2 : FS * sh.cw;
+    const int step0 = SPLIT ? wave * my_steps : 0;
+    const int r0 = FS == 1 ? 0 : (step0 >= sh.cw) + (step0 >= 2 * sh.cw);
+    const int w0 = step0 - r0 * sh.cw;
+    const unsigned piece0 = piece_of(n, oh, ow0);
+    unsigned x_off = piece0 + (unsigned)w0 * x_wstep + (unsigned)(r0 * sh.Wp * KA);
+    unsigned q_off = (unsigned)((r0 * FS * sh.cw + w0) * QSTEP);
     const unsigned x_rwrap = (unsigned)sh.Wp * KA - (unsigned)(sh.cw - 1) * x_wstep;   // first word of the next filter row
     const unsigned q_rwrap = (unsigned)((FS - 1) * sh.cw * QSTEP + QSTEP);
     const unsigned q_tap = (unsigned)(sh.cw * QSTEP);
@@ -197,11 +203,11 @@ bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
     //    generation of resident waves - so that tile finds them in the L2 when it starts.
     constexpr int PF_LINES = IMG ? P : (XN - 1 + 31) / 32 + 1;
     const __amdgpu_buffer_rsrc_t abuf = raw_buffer(act, sh.act_bytes);
-    auto touch = [&](unsigned piece0, uint32_t (&pf)[PF_LINES]) {
+    auto touch = [&](unsigned tile_piece, uint32_t (&pf)[PF_LINES]) {
         const int steps = my_steps;               // <= 64 (launcher)
-        const int sl = (int)lane < steps ? (int)lane : steps - 1;
-        const int r = (sl >= sh.cw) + (sl >= 2 * sh.cw);
-        const unsigned piece = piece0 + (unsigned)(sl - r * sh.cw) * x_wstep + (unsigned)(r * sh.Wp * KA);
+        const int sl = step0 + ((int)lane < steps ? (int)lane : steps - 1);
+        const int r = FS == 1 ? 0 : (sl >= sh.cw) + (sl >= 2 * sh.cw);
+        const unsigned piece = tile_piece + (unsigned)(sl - r * sh.cw) * x_wstep + (unsigned)(r * sh.Wp * KA);
 #pragma unroll
         for (int ln = 0; ln < PF_LINES; ++ln) {
             const unsigned e = IMG ? (unsigned)ln * img_step : (unsigned)(ln * 32 < XN - 1 ? ln * 32 : XN - 1);
@@ -209,11 +215,11 @@ bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
         }
     };
     uint32_t pf_own[PF_LINES], pf_ahead[PF_LINES];
-    const int die_tile = (int)(blockIdx.x >> 3) * 4 + wave;           // index among the die's tiles
-    // (image runs: small grids, every wave is among the first of its die)
-    const bool touch_own = IMG || (die_tile < sh.touch_ahead && FS * sh.cw > 2);  // (two steps are requested at once anyway)
-    if (touch_own) touch(x_off, pf_own);
-    const bool touch_next = !IMG && kg == 0 && die_tile + sh.touch_ahead < sh.xcd_chunk * 4 && tile + sh.touch_ahead < sh.ntiles;
+    const int die_tile = SPLIT ? (int)(blockIdx.x >> 3) : (int)(blockIdx.x >> 3) * 4 + wave;   // index among the die's tiles
+    const int die_tiles = SPLIT ? sh.xcd_chunk : sh.xcd_chunk * 4;
+    const bool touch_own = die_tile < sh.touch_ahead && my_steps > 2;     // (two steps are requested at once anyway)
+    if (touch_own) touch(piece0, pf_own);
+    const bool touch_next = kg == 0 && die_tile + sh.touch_ahead < die_tiles && tile + sh.touch_ahead < sh.ntiles;
     if (touch_next) {
         // touch_ahead is a multiple of the channel groups: the tile ahead is channel group 0 of its positions
         const int ptile_a = ptile + sh.touch_ahead_pos;
@@ -225,7 +231,7 @@ bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
         if (ow_a > sh.OW - P) ow_a = sh.OW - P;
         touch(piece_of(n_a, oh_a, ow_a), pf_ahead);
     }
-    int w_next = 0;                               // word index of the step the offsets point at
+    int w_next = w0;                              // word index of the step the offsets point at
     int left = my_steps;                          // steps not yet requested
     // request the operands of the step the offsets point at (one scalar piece of input, one per-lane load per
     // tap that brings the k_w planes), then move the offsets one step on - without a branch, so that the loop
@@ -338,7 +344,7 @@ bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
         }
         return;
     }
-    if constexpr (IMG) {
+    if constexpr (SPLIT) {
         // ---- Eq. 14 over the wave's quarter of the reduction; the quarters meet in LDS, and wave w finishes
         //      positions w, w + 4, ... (sum of the four quarters, affine epilogue, 64 consecutive values each)
         __shared__ uint32_t part[4][P][64];
@@ -350,15 +356,16 @@ bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
             part[wave][p][lane] = v;
         }
         __syncthreads();
-        const size_t o0 = (size_t)ow0 * sh.K + (size_t)(kg * 64);
+        const size_t o0 = ((size_t)grow * sh.OW + ow0) * sh.K + (size_t)(kg * 64);
         const unsigned prow = (unsigned)sh.K * 4u;
         const unsigned span = (unsigned)(P - 1) * prow + (unsigned)(sh.K - kg * 64 < 64 ? sh.K - kg * 64 : 64) * 4u;
         const __amdgpu_buffer_rsrc_t ibuf = raw_buffer(acc_out + o0, span);
         const __amdgpu_buffer_rsrc_t fbuf = raw_buffer(out_f32 ? out_f32 + o0 : nullptr, out_f32 ? span : 0u);
         if (k < sh.K) {
 #pragma unroll
-            for (int pp = 0; pp < P / 4; ++pp) {
+            for (int pp = 0; pp < (P + 3) / 4; ++pp) {
                 const int p = wave + 4 * pp;
+                if (p >= P) break;
                 const uint32_t v = part[0][p][lane] + part[1][p][lane] + part[2][p][lane] + part[3][p][lane];
                 __builtin_amdgcn_raw_buffer_store_b32(v, ibuf, (int)lane4, (int)((unsigned)p * prow), 0);
                 if (out_f32)
@@ -405,20 +412,19 @@ template <int KW, int KA, int ST, int FS = 3> struct LaneRun {
     static constexpr int SMALL = ST == 1 ? 7 : 4;
 };
 
-template <int KW, int KA, int P, int ST, int FS, bool REQ>
+template <int KW, int KA, int P, int ST, int FS, bool REQ, bool SPLIT = false>
 static int launch_lane_cfg(const ConvArgs &a)
 {
     constexpr bool IMG = ST == 0;       // runs over images: one output position per image
     if (a.wtop || (a.next != nullptr) != REQ) return EBS_ERR_UNSUPPORTED;
     if (a.R != FS || a.S != FS || a.pad > kActBorder) return EBS_ERR_UNSUPPORTED;
     if (IMG ? (a.OH != 1 || a.OW != 1 || a.N < P) : (a.stride != ST || a.OW < P)) return EBS_ERR_UNSUPPORTED;
-    static_assert(!IMG || P % 4 == 0, "image runs: each of the four waves finishes P / 4 positions");
     // image runs: the batch is described to the kernel as one output row of N positions
     const int rows = IMG ? 1 : a.N * a.OH;
     const int row_len = IMG ? a.N : a.OW;
     // the loop takes two steps (filter row, word) per trip; one lane per step touches the step's input piece
-    // (image runs: per wave, a quarter of the words)
-    if (IMG ? ((a.cw & 7) || a.cw > 256) : (((FS * a.cw) & 1) || FS * a.cw > 64)) return EBS_ERR_UNSUPPORTED;
+    // (split reduction: per wave, a quarter of the steps)
+    if (SPLIT ? (((FS * a.cw) & 7) || FS * a.cw > 256) : (((FS * a.cw) & 1) || FS * a.cw > 64)) return EBS_ERR_UNSUPPORTED;
     constexpr int FSZ = FS * FS;
     LaneShape sh{};
     sh.K = a.K; sh.cw = a.cw; sh.OH = IMG ? 1 : a.OH; sh.OW = row_len;
@@ -457,20 +463,27 @@ static int launch_lane_cfg(const ConvArgs &a)
     const DeviceShape *dev = device_shape();
     if (!dev) return EBS_ERR_HIP;
     if (!dev->gfx950) return EBS_ERR_UNSUPPORTED;       // run lengths and die numbering are gfx950's
-    const long long wgs = IMG ? ntiles : (ntiles + 3) / 4;
+    const long long wgs = SPLIT ? ntiles : (ntiles + 3) / 4;
     sh.xcd_chunk = (int)((wgs + 7) / 8);
     // one generation of resident waves of a die: 32 compute units x 4 SIMDs x 8 waves
-    sh.touch_ahead_pos = (dev->cus / 8 * 32 + sh.kgroups - 1) / sh.kgroups;
+    sh.touch_ahead_pos = (dev->cus / 8 * 32 / (SPLIT ? 4 : 1) + sh.kgroups - 1) / sh.kgroups;
     sh.touch_ahead = sh.touch_ahead_pos * sh.kgroups;
-    hipLaunchKernelGGL((bd_conv_lane<KW, KA, P, ST, FS, REQ>), dim3((unsigned)(sh.xcd_chunk * 8)), dim3(256), 0, a.stream,
+    hipLaunchKernelGGL((bd_conv_lane<KW, KA, P, ST, FS, REQ, SPLIT>), dim3((unsigned)(sh.xcd_chunk * 8)), dim3(256), 0, a.stream,
                        a.act, a.wgt, a.scale, a.offset, a.acc, a.out, a.next, sh);
     return hip_ok(hipGetLastError());
 }
 
-// sel: 0 = large runs, 1 = small runs
+// sel: 0 = large runs, 1 = small runs, 2 = small runs with the reduction split among a work-group's waves
 template <int KW, int KA, int FS, bool REQ>
 static int launch_lane_fs(const ConvArgs &a, int sel)
 {
+    if (sel == 2) {
+        if constexpr (!REQ) {
+            if (a.stride == 1) return launch_lane_cfg<KW, KA, LaneRun<KW, KA, 1, FS>::SMALL, 1, FS, false, true>(a);
+            if (a.stride == 2 && FS == 3) return launch_lane_cfg<KW, KA, LaneRun<KW, KA, 2, FS>::BIG, 2, FS, false, true>(a);
+        }
+        return EBS_ERR_UNSUPPORTED;
+    }
     if (a.stride == 1) {
         if (sel == 0) return launch_lane_cfg<KW, KA, LaneRun<KW, KA, 1, FS>::BIG, 1, FS, REQ>(a);
         return launch_lane_cfg<KW, KA, LaneRun<KW, KA, 1, FS>::SMALL, 1, FS, REQ>(a);
@@ -486,8 +499,8 @@ static int launch_lane_fs(const ConvArgs &a, int sel)
 template <int KW, int KA>
 static int launch_lane_images(const ConvArgs &a, int sel)
 {
-    if (sel == 0) return launch_lane_cfg<KW, KA, 8, 0, 1, false>(a);
-    return launch_lane_cfg<KW, KA, 4, 0, 1, false>(a);
+    if (sel == 0) return launch_lane_cfg<KW, KA, 8, 0, 1, false, true>(a);
+    return launch_lane_cfg<KW, KA, 4, 0, 1, false, true>(a);
 }
 
 template <int KW, int KA>

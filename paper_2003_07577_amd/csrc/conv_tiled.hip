@@ -26,9 +26,10 @@ static const char *const kNames[] = {
     "k4.wide.ch2", "k4.wide.ch1", "k4.wide.ch4",
     "lane.big", "lane.small",
     "pair",
+    "lane.split",
 };
 static constexpr int kNumVariants = sizeof(kNames) / sizeof(kNames[0]);
-enum { V_P4_64 = 0, V_P4_32 = 3, V_K4_64 = 6, V_K4_32 = 9, V_K4_16 = 12, V_R4_64 = 15, V_R4_32 = 16, V_R4_16 = 17, V_K4_WIDE = 18, V_LANE = 21, V_PAIR = 23 };
+enum { V_P4_64 = 0, V_P4_32 = 3, V_K4_64 = 6, V_K4_32 = 9, V_K4_16 = 12, V_R4_64 = 15, V_R4_32 = 16, V_R4_16 = 17, V_K4_WIDE = 18, V_LANE = 21, V_PAIR = 23, V_LANE_SPLIT = 24 };
 
 int conv_tiled_variant_count() { return kNumVariants; }
 const char *conv_tiled_variant_name(int v) { return (v >= 0 && v < kNumVariants) ? kNames[v] : "invalid"; }
@@ -56,6 +57,7 @@ static int run_variant(const ConvArgs &a, int v)
 {
     if (v < 0 || v >= kNumVariants) return EBS_ERR_UNSUPPORTED;
     if (v == V_PAIR) return launch_conv_pair(a);
+    if (v == V_LANE_SPLIT) return launch_conv_lane(a, 2);
     if (v >= V_LANE) return launch_conv_lane(a, v - V_LANE);
     if (a.R == 3 && a.S == 3) return run_fs<3>(a, v);     // unrolled 3x3 taps
     return run_fs<0>(a, v);
@@ -140,19 +142,49 @@ static int lane_choice(const ConvArgs &a)
     // reduction and fewer pairs are bound by their output writes and do as well or better with the wide tiles.
     // Measured on the ResNet-50 bottleneck shapes at (2,4), (3,3), (4,2): -3..-10 % (256->64 @56x56), -10 %
     // (1024->256 @14x14), -7..-10 % (256->1024 @14x14), -17 % (64->256 @56x56 at (3,3)).
-    if (rs == 1 && a.kw <= 4 && a.ka <= 4 && !a.wtop && positions >= 8192 && (a.cw & 1) == 0 && a.K % 64 == 0 &&
-        (a.cw >= 8 || a.kw * a.ka >= 8)) {
-        return 1;
+    // Layers with fewer positions as long as the rows hold a run: 512->2048 @7x7 16.3 / 54.6 / 92.0 us at (1,1) /
+    // (3,3) / (4,4) against 23.6 / 63.8 / 102.2 us of the best tiling.
+    if (rs == 1 && a.kw <= 4 && a.ka <= 4 && !a.wtop && (a.cw & 1) == 0 && a.K % 64 == 0 && (a.cw >= 8 || a.kw * a.ka >= 8)) {
+        const int run = lane_run_length(a.kw, a.ka, a.stride, 1, 1);
+        if (positions >= 8192 ||
+            (positions >= 2048 && run > 0 && a.OW >= run && (long long)((a.OW + run - 1) / run) * run * 100 <= (long long)a.OW * 115))
+            return 1;
     }
     // One output position per image (a fully-connected layer): runs of images, the reduction split among the
     // four waves of a work-group.  Measured on 2048 -> 1000 at batch 1024 against the best tiling: 61.7 vs 75 us
-    // at (4,4), 39.7 vs 51 at (3,3), 22 vs 33 at (2,2), 24 vs 33 at (1,4), 20.9 vs 31 at (4,1), 14.4 vs 18.5 at (1,1).
+    // at (4,4), 39.7 vs 51 at (3,3), 22 vs 33 at (2,2), 24 vs 33 at (1,4), 20.9 vs 31 at (4,1), 14.4 vs 18.5 at (1,1);
+    // 4096 -> 4096 at batch 128: 21.4 vs 41.3 us at (2,2), 62.7 vs 91.2 at (4,4).
     if (rs == 1 && a.OH == 1 && a.OW == 1 && !a.next && a.kw <= 4 && a.ka <= 4 && !a.wtop && (a.cw & 7) == 0 &&
-        a.cw <= 256 && a.N >= 256 && (long long)((a.K + 63) / 64) * 64 * 100 <= (long long)a.K * 115) {
+        a.cw <= 256 && a.N >= 64 && (long long)((a.K + 63) / 64) * 64 * 100 <= (long long)a.K * 115) {
         // runs of 8 images for one-bit activations (little arithmetic per step), else 4 (8 were 7-33 % slower)
         return a.ka == 1 ? 0 : 1;
     }
     return -1;
+}
+
+// Channel-per-lane kernel with the reduction split among the four waves of a work-group: 3x3 layers with few
+// positions and at least 256 input channels, where a wave of the unsplit kernel is one long chain of dependent
+// steps.  Measured on the ResNet-18 shapes against the choice below it: 512 @7x7 -3..-9 % up to six plane pairs
+// and at (3,3), +-1 % at eight and sixteen; 256->512 @14x14 stride 2 -7..-9 % with one- or two-bit activations
+// (runs of seven positions; equal at (1,1)), +3..+8 % with more (runs of four recompute an eighth of the row).
+static bool split_choice(const ConvArgs &a)
+{
+    const long long positions = (long long)a.N * a.OH * a.OW;
+    const int pairs = a.kw * a.ka;
+    if (a.next || a.wtop || a.R != a.S || (a.R != 3 && a.R != 1) || a.kw > 4 || a.ka > 4 || (a.cw & 7) || a.R * a.cw > 256)
+        return false;
+    if (positions < 2048 || (a.K % 64 != 0 && a.K < 256)) return false;
+    const int run = lane_run_length(a.kw, a.ka, a.stride, a.R, a.stride == 1 ? 1 : 0);
+    if (run <= 0 || a.OW < run || (long long)((a.OW + run - 1) / run) * run * 100 > (long long)a.OW * 115) return false;
+    // only where the unsplit kernel would have at most four waves per SIMD (3584 on the layers above; with 7168
+    // or 14336 - 256 @14x14, 1x1 1024->256 @14x14, 1x1 512->2048 @7x7 - the unsplit kernel is faster)
+    if ((long long)a.N * a.OH * ((a.OW + run - 1) / run) * ((a.K + 63) / 64) > 4096) return false;
+    // 1x1 filters (stride 1): 2048->512 @7x7 15.7 / 28.3 / 54.4 / 91.2 us at (1,1) / (2,2) / (3,3) / (4,4) against
+    // 30.1 / 40.9 / 71.4 / 114.7 us of the best tiling (unsplit channel-per-lane kernel: 16.8 / 33.6 / 64.1 / 105.8)
+    if (a.R == 1) return a.stride == 1;
+    if (a.stride == 1) return pairs <= 6 || pairs == 9;
+    if (a.stride == 2) return a.ka <= 2 && pairs >= 2;
+    return false;
 }
 
 // Fused re-quantisation: the K4 kernels whose work-groups own whole 32-channel words; layers with few
@@ -199,11 +231,12 @@ int launch_conv_tiled(const ConvArgs &a, int variant)
     const long long positions = (long long)a.N * a.OH * a.OW;
     const int slot = ch_slot(a.cw);
     const int rs = a.R * a.S;
-    int order[13];
+    int order[14];
     int n = 0;
     // 3x3 layers with at most 16 input channels: two taps per word (half the AND + bitcount work of the
     // one-tap-per-word kernels, whose words are half zeros there)
     if (a.C <= 16 && rs == 9 && a.R == 3 && a.K <= 32) order[n++] = V_PAIR;
+    if (split_choice(a)) order[n++] = V_LANE_SPLIT;
     {
         const int sel = lane_choice(a);
         if (sel >= 0) {

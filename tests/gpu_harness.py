@@ -28,6 +28,7 @@ VARIANT_GEOS = [  # N, C, H, W, K, R, S, stride, pad
     (2, 12, 9, 11, 20, 3, 3, 2, 1),       # fewer than 16 input channels, stride 2, K ragged against the 32 channel lanes
     (1, 7, 6, 5, 3, 3, 3, 1, 0),          # no padding, a single partial tile
     (301, 256, 1, 1, 200, 1, 1, 1, 0),    # fully-connected: one position per image, batch and K ragged
+    (2, 256, 15, 16, 130, 3, 3, 2, 1),    # deep reduction at stride 2 (rows of 8 outputs), K ragged vs 64
 ]
 MUST_ACCEPT = [
     {"p4.tile32.ch2", "k4.tile16.ch2", "k4.tile16.ch1", "k4.tile32.ch2"},
@@ -42,11 +43,12 @@ MUST_ACCEPT = [
     {"pair", "p4.tile32.ch1"},
     {"pair", "p4.tile32.ch1"},
     {"p4.tile32.ch4", "k4.tile16.ch4"},
+    {"p4.tile32.ch4", "k4.tile16.ch4", "r4.tile16.ch4"},
 ]
 # the channel-per-lane kernel (3x3 and 1x1 filters, bitwidths up to four, an even number of reduction steps):
 # shapes whose rows hold a short run
-MUST_ACCEPT_LANE = [{"lane.small"}, {"lane.small"}, set(), set(), {"lane.small"}, set(), {"lane.small"}, {"lane.small"},
-                    set(), set(), set(), {"lane.big", "lane.small"}]
+MUST_ACCEPT_LANE = [{"lane.small"}, {"lane.small"}, set(), set(), {"lane.small", "lane.split"}, set(), {"lane.small"},
+                    {"lane.small"}, set(), set(), set(), {"lane.big", "lane.small", "lane.split"}, {"lane.small", "lane.split"}]
 
 
 def unpack_weight_pairs(words, K, C, k_w):

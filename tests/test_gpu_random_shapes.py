@@ -186,3 +186,37 @@ def test_random_fully_connected_shapes_forced_image_runs(oracle_mod, block):
             assert np.array_equal(d["acc"].cpu().numpy(), ref), (tag, name)
             assert_f32_close(d["out"].cpu().numpy(), fref, ref, inp["scale"], inp["per_channel"])
     assert ran["lane.big"] >= 6 and ran["lane.small"] >= 6, ran
+
+
+@pytest.mark.parametrize("block", range(2))
+def test_random_deep_layers_forced_split_reduction(oracle_mod, block):
+    """3x3 layers with 256 or 512 input channels through the channel-per-lane kernel whose four waves split the
+    reduction (forced by variant; a wave's quarter starts inside a filter row or wraps into the next one)."""
+    import torch
+    v = {ebs.ebs_conv_variant_name(i): i for i in range(ebs.ebs_conv_variant_count() + 1)}["lane.split"]
+    rng = np.random.default_rng(5151 + block)
+    ran = 0
+    for i in range(8):
+        C, st, pad = int(rng.choice([256, 512])), int(rng.integers(1, 3)), int(rng.integers(0, 2))
+        N, H, W = int(rng.integers(1, 4)), int(rng.integers(5, 15)), int(rng.integers(9, 20)) * st
+        K = int(rng.choice([40, 64, 70, 128, 200]))
+        kw, ka = int(rng.integers(1, 5)), int(rng.integers(1, 5))
+        inp = wl.random_case(int(rng.integers(1 << 30)), N, C, H, W, K, 3, 3, st, pad, kw, ka,
+                             per_channel=bool(rng.integers(0, 2)), with_offset=bool(rng.integers(0, 2)))
+        tag = f"block{block}.{i} N{N} C{C} H{H} W{W} K{K} s{st} p{pad} w{kw} a{ka}"
+        print(f"[case] {tag}", flush=True)
+        d = upload(inp, kw, ka, st, pad)
+        pack(d)
+        g = d["g"]
+        d["acc"].fill_(POISON)
+        d["out"].fill_(float("nan"))
+        rc = ebs.ebs_mixed_conv2d_variant(v, d["pa"], d["pw"], g["N"], g["C"], g["H"], g["W"], g["K"], 3, 3, st, pad, kw, ka,
+                                          d["scale"], d["offset"], d["per_channel"], d["acc"], d["out"], check=False)
+        assert rc == 0, (tag, rc)
+        torch.cuda.synchronize()
+        ran += 1
+        ref = oracle_mod.conv2d_levels(inp["a"], inp["q"], st, pad)
+        fref = oracle_mod.dequant(ref, inp["scale"], inp["offset"], inp["per_channel"])
+        assert np.array_equal(d["acc"].cpu().numpy(), ref), tag
+        assert_f32_close(d["out"].cpu().numpy(), fref, ref, inp["scale"], inp["per_channel"])
+    assert ran == 8
