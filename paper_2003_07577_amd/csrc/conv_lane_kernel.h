@@ -125,7 +125,7 @@ bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
     constexpr int NCLS = KW + KA - 1;
     constexpr bool IMG = ST == 0;                 // runs over images (1x1 filter, one output position per image)
     static_assert(!IMG || (FS == 1 && SPLIT), "image runs: 1x1 filters, split reduction");
-    static_assert(!SPLIT || !REQ, "split reduction: plain outputs");
+    static_assert(!IMG || !REQ, "image runs: plain outputs");
     constexpr int XST = IMG ? 1 : ST;             // distance of consecutive positions in a step's registers
     constexpr int NSEG = (P - 1) * XST + FS;      // input positions one filter row of the run touches
     constexpr int XN = NSEG * KA;                 // dwords of one step's input piece
@@ -321,7 +321,7 @@ bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
         for (int ln = 0; ln < PF_LINES; ++ln) asm volatile("" ::"v"(pf_ahead[ln]));
     }
 
-    if constexpr (REQ) {
+    if constexpr (REQ && !SPLIT) {
         // ---- Eq. 14, the affine map and the next layer's quantiser; lanes 0 and 32 store the two words of a plane
         const size_t posn = ((size_t)n * sh.OHn + oh + kActBorder) * sh.OWn + ow0 + kActBorder;
         const int wd = kg * 2 + (int)(lane >> 5);
@@ -356,6 +356,30 @@ bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
             part[wave][p][lane] = v;
         }
         __syncthreads();
+        if constexpr (REQ) {
+            // the affine map and the next layer's quantiser on the wave's positions; the ballot of level bit j over
+            // the 64 channel lanes is the pair of words of plane j, stored by lanes 0 and 32
+            const size_t posn = ((size_t)n * sh.OHn + oh + kActBorder) * sh.OWn + ow0 + kActBorder;
+            const int wd = kg * 2 + (int)(lane >> 5);
+            const bool writer = (lane & 31u) == 0u && wd < sh.cwn;
+            uint32_t *dst = packed_next + ((size_t)wd * sh.total_next + posn) * sh.k_next;
+#pragma unroll
+            for (int pp = 0; pp < (P + 3) / 4; ++pp) {
+                const int p = wave + 4 * pp;
+                if (p >= P) break;
+                const uint32_t v = part[0][p][lane] + part[1][p][lane] + part[2][p][lane] + part[3][p][lane];
+                const uint32_t lv = k < sh.K ? requant_level((int32_t)v, sc, of, sh.alpha, sh.qs) : 0u;
+#pragma unroll
+                for (int j = 0; j < kMaxBits; ++j) {
+                    if (j < sh.k_next) {
+                        const unsigned long long m = __ballot((lv >> j) & 1u);
+                        const uint32_t word = (lane >> 5) ? (uint32_t)(m >> 32) : (uint32_t)m;
+                        if (writer) dst[(size_t)p * sh.k_next + j] = word;
+                    }
+                }
+            }
+            return;
+        }
         const size_t o0 = ((size_t)grow * sh.OW + ow0) * sh.K + (size_t)(kg * 64);
         const unsigned prow = (unsigned)sh.K * 4u;
         const unsigned span = (unsigned)(P - 1) * prow + (unsigned)(sh.K - kg * 64 < 64 ? sh.K - kg * 64 : 64) * 4u;
@@ -478,10 +502,8 @@ template <int KW, int KA, int FS, bool REQ>
 static int launch_lane_fs(const ConvArgs &a, int sel)
 {
     if (sel == 2) {
-        if constexpr (!REQ) {
-            if (a.stride == 1) return launch_lane_cfg<KW, KA, LaneRun<KW, KA, 1, FS>::SMALL, 1, FS, false, true>(a);
-            if (a.stride == 2 && FS == 3) return launch_lane_cfg<KW, KA, LaneRun<KW, KA, 2, FS>::BIG, 2, FS, false, true>(a);
-        }
+        if (a.stride == 1) return launch_lane_cfg<KW, KA, LaneRun<KW, KA, 1, FS>::SMALL, 1, FS, REQ, true>(a);
+        if (a.stride == 2 && FS == 3) return launch_lane_cfg<KW, KA, LaneRun<KW, KA, 2, FS>::BIG, 2, FS, REQ, true>(a);
         return EBS_ERR_UNSUPPORTED;
     }
     if (a.stride == 1) {

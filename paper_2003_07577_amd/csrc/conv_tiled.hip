@@ -171,7 +171,7 @@ static bool split_choice(const ConvArgs &a)
 {
     const long long positions = (long long)a.N * a.OH * a.OW;
     const int pairs = a.kw * a.ka;
-    if (a.next || a.wtop || a.R != a.S || (a.R != 3 && a.R != 1) || a.kw > 4 || a.ka > 4 || (a.cw & 7) || a.R * a.cw > 256)
+    if (a.wtop || a.R != a.S || (a.R != 3 && a.R != 1) || a.kw > 4 || a.ka > 4 || (a.cw & 7) || a.R * a.cw > 256)
         return false;
     if (positions < 2048 || (a.K % 64 != 0 && a.K < 256)) return false;
     const int run = lane_run_length(a.kw, a.ka, a.stride, a.R, a.stride == 1 ? 1 : 0);
@@ -182,7 +182,9 @@ static bool split_choice(const ConvArgs &a)
     // 1x1 filters (stride 1): 2048->512 @7x7 15.7 / 28.3 / 54.4 / 91.2 us at (1,1) / (2,2) / (3,3) / (4,4) against
     // 30.1 / 40.9 / 71.4 / 114.7 us of the best tiling (unsplit channel-per-lane kernel: 16.8 / 33.6 / 64.1 / 105.8)
     if (a.R == 1) return a.stride == 1;
-    if (a.stride == 1) return pairs <= 6 || pairs == 9;
+    // (re-quantising: the tiled kernels that split the reduction are slower than their plain forms, 230 vs 199 us
+    // on 512 @7x7 at (4,4), so there all pairs)
+    if (a.stride == 1) return a.next || pairs <= 6 || pairs == 9;
     if (a.stride == 2) return a.ka <= 2 && pairs >= 2;
     return false;
 }
@@ -199,6 +201,10 @@ int launch_requant_tiled(const ConvArgs &a)
         if (rc != EBS_ERR_UNSUPPORTED) return rc;
     }
     // the channel-per-lane kernel where the plain convolution would use it (unsigned weights only)
+    if (split_choice(a)) {
+        const int rc = launch_conv_lane(a, 2);
+        if (rc != EBS_ERR_UNSUPPORTED) return rc;
+    }
     if (!a.wtop) {
         const int sel = lane_choice(a);
         if (sel >= 0) {

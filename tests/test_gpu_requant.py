@@ -54,6 +54,9 @@ GEOS = [  # N, C, H, W, K, R, S, stride, pad
     (8, 64, 40, 28, 260, 3, 3, 1, 1),     # 8960 positions: the channel-per-lane kernel (unsigned weights), K ragged vs 64 and 32
     (16, 64, 48, 56, 128, 3, 3, 2, 1),    # the same at stride 2
     (8, 256, 34, 32, 64, 1, 1, 1, 0),     # 1x1 with eight reduction words: lane kernel too
+    (16, 256, 14, 14, 260, 3, 3, 1, 1),   # 3136 positions, eight words: lane kernel, reduction split among the waves
+    (12, 256, 28, 28, 64, 3, 3, 2, 1),    # the same at stride 2 (runs of seven with one- or two-bit activations)
+    (48, 512, 7, 7, 64, 1, 1, 1, 0),      # 1x1, sixteen words, 2352 positions: split as well
 ]
 
 
