@@ -231,6 +231,44 @@ bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
         if (ow_a > sh.OW - P) ow_a = sh.OW - P;
         touch(piece_of(n_a, oh_a, ow_a), pf_ahead);
     }
+    // REQ: what the epilogue needs of the next layer's tensor is worked out here and parked in vector registers
+    // (the scalar registers are what the two input buffers of the reduction need): the address of the wave's
+    // first output word, the distance to the second word of a plane for lanes 32-63, the writer lanes, the quantiser
+    uint32_t rq_base_lo = 0, rq_base_hi = 0, rq_span = 0, rq_voff = 0, rq_k = 0, rq_flags = 0;
+    float rq_alpha = 0.0f, rq_qs = 0.0f;
+    if constexpr (REQ) {
+        const size_t posn = ((size_t)n * sh.OHn + oh + kActBorder) * sh.OWn + ow0 + kActBorder;
+        const size_t word_dwords = (size_t)sh.total_next * sh.k_next;       // from a word's planes to the next word's
+        const uint64_t base = (uint64_t)(packed_next + (size_t)(kg * 2) * word_dwords + posn * sh.k_next);
+        rq_base_lo = (uint32_t)base;
+        rq_base_hi = (uint32_t)(base >> 32);
+        rq_span = (uint32_t)((word_dwords + (size_t)P * sh.k_next) * 4);    // (launcher: below 2^31)
+        rq_voff = (lane >> 5) ? (uint32_t)(word_dwords * 4) : 0u;
+        rq_k = (uint32_t)sh.k_next;
+        rq_flags = (((lane & 31u) == 0u && kg * 2 + (int)(lane >> 5) < sh.cwn) ? 1u : 0u) | (k < sh.K ? 2u : 0u);
+        rq_alpha = sh.alpha;
+        rq_qs = sh.qs;
+        asm volatile("" : "+v"(rq_base_lo), "+v"(rq_base_hi), "+v"(rq_span), "+v"(rq_voff), "+v"(rq_k), "+v"(rq_flags),
+                          "+v"(rq_alpha), "+v"(rq_qs));
+    }
+    // the affine map and the next layer's quantiser on position p of the run; the ballot of level bit j over the
+    // 64 channel lanes is the pair of 32-channel words of plane j, stored by lanes 0 and 32
+    auto requant_store = [&](int p, uint32_t v, __amdgpu_buffer_rsrc_t nbuf, int k_next) {
+        const uint32_t lv = (rq_flags & 2u) ? requant_level((int32_t)v, sc, of, rq_alpha, rq_qs) : 0u;
+#pragma unroll
+        for (int j = 0; j < kMaxBits; ++j) {
+            if (j < k_next) {
+                const unsigned long long m = __ballot((lv >> j) & 1u);
+                const uint32_t word = (lane >> 5) ? (uint32_t)(m >> 32) : (uint32_t)m;
+                if (rq_flags & 1u)
+                    __builtin_amdgcn_raw_buffer_store_b32(word, nbuf, (int)rq_voff, (int)((unsigned)(p * k_next + j) * 4u), 0);
+            }
+        }
+    };
+    auto requant_buffer = [&]() {
+        const uint64_t base = ((uint64_t)(uint32_t)uni((int)rq_base_hi) << 32) | (uint32_t)uni((int)rq_base_lo);
+        return raw_buffer(reinterpret_cast<const void *>(base), (unsigned)uni((int)rq_span));
+    };
     int w_next = w0;                              // word index of the step the offsets point at
     int left = my_steps;                          // steps not yet requested
     // request the operands of the step the offsets point at (one scalar piece of input, one per-lane load per
@@ -322,25 +360,15 @@ bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
     }
 
     if constexpr (REQ && !SPLIT) {
-        // ---- Eq. 14, the affine map and the next layer's quantiser; lanes 0 and 32 store the two words of a plane
-        const size_t posn = ((size_t)n * sh.OHn + oh + kActBorder) * sh.OWn + ow0 + kActBorder;
-        const int wd = kg * 2 + (int)(lane >> 5);
-        const bool writer = (lane & 31u) == 0u && wd < sh.cwn;
-        uint32_t *dst = packed_next + ((size_t)wd * sh.total_next + posn) * sh.k_next;
+        // ---- Eq. 14, then the next layer's levels and bit planes
+        const __amdgpu_buffer_rsrc_t nbuf = requant_buffer();
+        const int k_next = uni((int)rq_k);
 #pragma unroll
         for (int p = 0; p < P; ++p) {
             uint32_t v = cls[p][0];
 #pragma unroll
             for (int c = 1; c < NCLS; ++c) v += cls[p][c] << c;
-            const uint32_t lv = k < sh.K ? requant_level((int32_t)v, sc, of, sh.alpha, sh.qs) : 0u;
-#pragma unroll
-            for (int j = 0; j < kMaxBits; ++j) {
-                if (j < sh.k_next) {
-                    const unsigned long long m = __ballot((lv >> j) & 1u);
-                    const uint32_t word = (lane >> 5) ? (uint32_t)(m >> 32) : (uint32_t)m;
-                    if (writer) dst[(size_t)p * sh.k_next + j] = word;
-                }
-            }
+            requant_store(p, v, nbuf, k_next);
         }
         return;
     }
@@ -357,26 +385,14 @@ bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
         }
         __syncthreads();
         if constexpr (REQ) {
-            // the affine map and the next layer's quantiser on the wave's positions; the ballot of level bit j over
-            // the 64 channel lanes is the pair of words of plane j, stored by lanes 0 and 32
-            const size_t posn = ((size_t)n * sh.OHn + oh + kActBorder) * sh.OWn + ow0 + kActBorder;
-            const int wd = kg * 2 + (int)(lane >> 5);
-            const bool writer = (lane & 31u) == 0u && wd < sh.cwn;
-            uint32_t *dst = packed_next + ((size_t)wd * sh.total_next + posn) * sh.k_next;
+            // the next layer's levels and bit planes of the wave's positions
+            const __amdgpu_buffer_rsrc_t nbuf = requant_buffer();
+            const int k_next = uni((int)rq_k);
 #pragma unroll
             for (int pp = 0; pp < (P + 3) / 4; ++pp) {
                 const int p = wave + 4 * pp;
                 if (p >= P) break;
-                const uint32_t v = part[0][p][lane] + part[1][p][lane] + part[2][p][lane] + part[3][p][lane];
-                const uint32_t lv = k < sh.K ? requant_level((int32_t)v, sc, of, sh.alpha, sh.qs) : 0u;
-#pragma unroll
-                for (int j = 0; j < kMaxBits; ++j) {
-                    if (j < sh.k_next) {
-                        const unsigned long long m = __ballot((lv >> j) & 1u);
-                        const uint32_t word = (lane >> 5) ? (uint32_t)(m >> 32) : (uint32_t)m;
-                        if (writer) dst[(size_t)p * sh.k_next + j] = word;
-                    }
-                }
+                requant_store(p, part[0][p][lane] + part[1][p][lane] + part[2][p][lane] + part[3][p][lane], nbuf, k_next);
             }
             return;
         }
@@ -479,6 +495,8 @@ static int launch_lane_cfg(const ConvArgs &a)
         sh.OWn = a.OW + 2 * kActBorder;
         sh.cwn = words_per_pixel(a.K);
         sh.total_next = a.N * sh.OHn * sh.OWn;
+        // (the epilogue addresses the second word of a plane by a 32-bit byte offset from the first)
+        if (((long long)sh.total_next + P) * a.k_next * 4 >= (1LL << 31)) return EBS_ERR_UNSUPPORTED;
         const long long per_image = (2LL * sh.OWn + 2LL * a.OH) * sh.cwn * a.k_next;
         if (per_image * a.N > (1LL << 30)) return EBS_ERR_UNSUPPORTED;
         sh.ring_per_image = (int)per_image;
@@ -503,7 +521,9 @@ static int launch_lane_fs(const ConvArgs &a, int sel)
 {
     if (sel == 2) {
         if (a.stride == 1) return launch_lane_cfg<KW, KA, LaneRun<KW, KA, 1, FS>::SMALL, 1, FS, REQ, true>(a);
-        if (a.stride == 2 && FS == 3) return launch_lane_cfg<KW, KA, LaneRun<KW, KA, 2, FS>::BIG, 2, FS, REQ, true>(a);
+        if constexpr (FS == 3) {
+            if (a.stride == 2) return launch_lane_cfg<KW, KA, LaneRun<KW, KA, 2, FS>::BIG, 2, FS, REQ, true>(a);
+        }
         return EBS_ERR_UNSUPPORTED;
     }
     if (a.stride == 1) {

@@ -120,6 +120,10 @@ static int lane_choice(const ConvArgs &a)
         } else if (positions >= 3072 && a.stride == 2) {
             use = pairs <= 6;
         }
+        // re-quantising: the tiled kernels own 8 instead of 4 channels per lane there, which costs them 8-14 % at
+        // the highest bitwidths; the lane kernel pays 2-3 % for its epilogue (measured: (4,4) -4..-6 % on 128 @28x28,
+        // 64->128 @56x56 s2, 256->512 @14x14 s2; stride 2 at (3,3)/(4,3) -2..-5 %; (3,4) +-3 %, left alone)
+        if (a.next && positions >= 3072 && (pairs == 16 || (a.stride == 2 && a.ka == 3 && a.kw >= 3))) use = true;
         if (use) {
             // small runs where the large ones leave fewer than six tiles per SIMD and divide the row
             const int big = lane_run_length(a.kw, a.ka, a.stride, a.R, 0), small = lane_run_length(a.kw, a.ka, a.stride, a.R, 1);
