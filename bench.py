@@ -259,6 +259,35 @@ def cpu_baseline(cases):
     }
 
 
+
+def vendor_int8_gemm_us(torch, dev, M, K, N):
+    """Microseconds per call of the vendor library's int8 GEMM (int32 result) on an M x K x N problem, timed as 20
+    calls in a captured graph replayed five times; None where this build of the framework has no such call."""
+    try:
+        a = torch.randint(-8, 8, (M, K), dtype=torch.int8, device=dev)
+        b = torch.randint(-8, 8, (K, N), dtype=torch.int8, device=dev)
+        c = torch.empty((M, N), dtype=torch.int32, device=dev)
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            torch._int_mm(a, b, out=c)
+            torch.cuda.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                for _ in range(20):
+                    torch._int_mm(a, b, out=c)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        ev[0].record()
+        for _ in range(5):
+            graph.replay()
+        ev[1].record()
+        torch.cuda.synchronize()
+        return ev[0].elapsed_time(ev[1]) * 1e3 / 100
+    except Exception:
+        return None
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -453,6 +482,13 @@ def main():
                 L = [c.layer for c in cases if c.tag == r["case"]][0]
                 if L in per_layer:
                     r["mfma_i8_us"] = round(per_layer[L], 2)
+            # the vendor library's int8 GEMM on each layer's GEMM shape, as context for the kernel above
+            vendor = {L.name: vendor_int8_gemm_us(torch, dev, L.N * L.OH * L.OW, L.R * L.S * L.C, L.K) for L in per_layer}
+            if all(v is not None for v in vendor.values()):
+                mfma["vendor_int8_gemm_us"] = {k: round(v, 1) for k, v in vendor.items()}
+                mfma["vendor_int8_gemm"] = ("torch._int_mm (the vendor GEMM library) on the layer as a plain GEMM, positions x "
+                                            "(filter taps * input channels) x output channels, operands already in matrix "
+                                            "form (no im2col pass, no epilogue), 20 launches in a captured graph")
 
     # ---- fused re-quantise + re-pack epilogue (replaces conv's 8 B/output and the next pack call)
     requant = None
