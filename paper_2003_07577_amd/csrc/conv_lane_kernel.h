@@ -39,6 +39,7 @@ struct LaneShape {
     int total_pos;      // N * plane_pos: positions per word of the packed input
     int origin;         // border - pad
     int runs;           // runs of P positions per output row
+    int runs_full;      // TAILED kernels: the first runs_full runs of a row hold P positions, the others P - 1
     int kgroups;        // ceil(K / 64)
     int ntiles;         // N*OH * runs * kgroups
     int xcd_chunk;      // ceil(work-groups / 8): work-groups of one die
@@ -112,10 +113,22 @@ template <> struct BufferLoad<4> {
     }
 };
 
+template <int I, int N, class F> __device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
 // REQ: instead of the int32 / fp32 outputs the kernel applies the next layer's activation quantiser (Eq. 1b-1c) and
 // writes the next layer's packed bit planes: a wave's 64 lanes are 64 consecutive channels, so the ballot of level
 // bit j over the wave IS the pair of 32-channel words of plane j; the work-groups also clear the zero ring.
-template <int KW, int KA, int P, int ST, int FS, bool REQ, bool SPLIT = false>
+// TAILED: rows whose length is no multiple of P are covered without overlap by runs of P and of P - 1 positions
+// (14 = 4 + 4 + 3 + 3).  A short run is a run of P that starts one position early and leaves its first position
+// out: all its loads stay inside the row, and the arithmetic and the store of that position are skipped (one
+// wave-uniform branch per step).
+template <int KW, int KA, int P, int ST, int FS, bool REQ, bool SPLIT = false, bool TAILED = false>
 __global__ void __launch_bounds__(256)
 bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
              const float *__restrict__ scale, const float *__restrict__ offset,
@@ -163,8 +176,20 @@ bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
     const int run = ptile - grow * sh.runs;
     const int n = (int)fd_div((uint32_t)grow, sh.div_oh);
     const int oh = grow - n * sh.OH;
-    int ow0 = run * P;
-    if (ow0 > sh.OW - P) ow0 = sh.OW - P;         // the last run of a row is moved left; the overlap is computed twice
+    // first position of a run, and whether the run leaves its first position out (TAILED).  Otherwise the last run
+    // of a row is moved left and the overlap is computed twice.
+    auto run_start = [&](int r, bool &short_run) {
+        int o = r * P;
+        short_run = false;
+        if constexpr (TAILED) {
+            short_run = r >= sh.runs_full;
+            if (short_run) o -= r - sh.runs_full + 1;
+        }
+        if (o > sh.OW - P) o = sh.OW - P;
+        return o;
+    };
+    bool skip0;
+    const int ow0 = run_start(run, skip0);
 
     const int k = kg * 64 + (int)lane;
     const int kc = k < sh.K ? k : sh.K - 1;
@@ -227,8 +252,8 @@ bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
         const int run_a = ptile_a - grow_a * sh.runs;
         const int n_a = (int)fd_div((uint32_t)grow_a, sh.div_oh);
         const int oh_a = grow_a - n_a * sh.OH;
-        int ow_a = run_a * P;
-        if (ow_a > sh.OW - P) ow_a = sh.OW - P;
+        bool short_a;
+        const int ow_a = run_start(run_a, short_a);
         touch(piece_of(n_a, oh_a, ow_a), pf_ahead);
     }
     // REQ: what the epilogue needs of the next layer's tensor is worked out here and parked in vector registers
@@ -295,14 +320,19 @@ bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
     };
 
     uint32_t cls[P][NCLS];
+    if constexpr (TAILED) {
+        // (a position that is left out is never accumulated: give its registers a value)
+#pragma unroll
+        for (int c = 0; c < NCLS; ++c) cls[0][c] = 0u;
+    }
     // Eq. 2 / Eq. 13 on one (filter row, word): the taps of the row for the P positions.  The very first step
     // writes every accumulator before it adds to it (shift class c first occurs at tap 0 with the smallest i).
     auto mac = [&](const uint32_t (&x)[XN], const uint32_t (&q)[FS][KW], auto first_step) {
         constexpr bool FIRST = decltype(first_step)::value;
+        auto position = [&](auto pc) {
+            constexpr int p = decltype(pc)::value;
 #pragma unroll
-        for (int s = 0; s < FS; ++s)
-#pragma unroll
-            for (int p = 0; p < P; ++p)
+            for (int s = 0; s < FS; ++s)
 #pragma unroll
                 for (int i = 0; i < KW; ++i)
 #pragma unroll
@@ -313,6 +343,26 @@ bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
                         else
                             cls[p][i + j] = lane_bcnt_acc(v, cls[p][i + j]);
                     }
+        };
+        if constexpr (TAILED) {
+            if (!skip0) position(std::integral_constant<int, 0>{});
+            static_for<1, P>(position);
+        } else {
+#pragma unroll
+            for (int s = 0; s < FS; ++s)
+#pragma unroll
+                for (int p = 0; p < P; ++p)
+#pragma unroll
+                    for (int i = 0; i < KW; ++i)
+#pragma unroll
+                        for (int j = 0; j < KA; ++j) {
+                            const uint32_t v = q[s][i] & x[(p * XST + s) * KA + j];
+                            if (FIRST && s == 0 && (i == 0 || j == KA - 1))
+                                cls[p][i + j] = lane_bcnt_first(v);
+                            else
+                                cls[p][i + j] = lane_bcnt_acc(v, cls[p][i + j]);
+                        }
+        }
     };
     using first_t = std::integral_constant<bool, true>;
     using later_t = std::integral_constant<bool, false>;
@@ -365,6 +415,7 @@ bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
         const int k_next = uni((int)rq_k);
 #pragma unroll
         for (int p = 0; p < P; ++p) {
+            if (TAILED && p == 0 && skip0) continue;       // (wave-uniform)
             uint32_t v = cls[p][0];
 #pragma unroll
             for (int c = 1; c < NCLS; ++c) v += cls[p][c] << c;
@@ -392,6 +443,7 @@ bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
             for (int pp = 0; pp < (P + 3) / 4; ++pp) {
                 const int p = wave + 4 * pp;
                 if (p >= P) break;
+                if (TAILED && p == 0 && skip0) continue;
                 requant_store(p, part[0][p][lane] + part[1][p][lane] + part[2][p][lane] + part[3][p][lane], nbuf, k_next);
             }
             return;
@@ -406,6 +458,7 @@ bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
             for (int pp = 0; pp < (P + 3) / 4; ++pp) {
                 const int p = wave + 4 * pp;
                 if (p >= P) break;
+                if (TAILED && p == 0 && skip0) continue;
                 const uint32_t v = part[0][p][lane] + part[1][p][lane] + part[2][p][lane] + part[3][p][lane];
                 __builtin_amdgcn_raw_buffer_store_b32(v, ibuf, (int)lane4, (int)((unsigned)p * prow), 0);
                 if (out_f32)
@@ -432,14 +485,18 @@ bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
         const unsigned span = (unsigned)(P - 1) * prow + (unsigned)(sh.K - kg * 64 < 64 ? sh.K - kg * 64 : 64) * 4u;
         const __amdgpu_buffer_rsrc_t ibuf = raw_buffer(acc_out + o0, span);
 #pragma unroll
-        for (int p = 0; p < P; ++p)
+        for (int p = 0; p < P; ++p) {
+            if (TAILED && p == 0 && skip0) continue;
             __builtin_amdgcn_raw_buffer_store_b32((uint32_t)acc[p], ibuf, (int)lane4, (int)((unsigned)p * prow), 0);
+        }
         if (out_f32) {
             const __amdgpu_buffer_rsrc_t fbuf = raw_buffer(out_f32 + o0, span);
 #pragma unroll
-            for (int p = 0; p < P; ++p)
+            for (int p = 0; p < P; ++p) {
+                if (TAILED && p == 0 && skip0) continue;
                 __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, fmaf((float)acc[p], sc, of)), fbuf,
                                                       (int)lane4, (int)((unsigned)p * prow), 0);
+            }
         }
     }
 }
@@ -450,9 +507,12 @@ template <int KW, int KA, int ST, int FS = 3> struct LaneRun {
     static constexpr int NCLS = KW + KA - 1;
     static constexpr int BIG = ST == 1 ? ((KA <= 2 && NCLS <= 4) ? 14 : 7) : (KA <= 2 ? 7 : 4);
     static constexpr int SMALL = ST == 1 ? 7 : 4;
+    // stride 2 with three or four activation bits has only the runs of four (scalar registers): rows of 14 or 7
+    // outputs are covered as 4 + 4 + 3 + 3 and 4 + 3
+    static constexpr bool TAILED = ST == 2 && KA >= 3;
 };
 
-template <int KW, int KA, int P, int ST, int FS, bool REQ, bool SPLIT = false>
+template <int KW, int KA, int P, int ST, int FS, bool REQ, bool SPLIT = false, bool TAILED = false>
 static int launch_lane_cfg(const ConvArgs &a)
 {
     constexpr bool IMG = ST == 0;       // runs over images: one output position per image
@@ -473,6 +533,12 @@ static int launch_lane_cfg(const ConvArgs &a)
     sh.total_pos = a.N * sh.plane_pos;
     sh.origin = kActBorder - a.pad;
     sh.runs = (row_len + P - 1) / P;
+    sh.runs_full = sh.runs;
+    if (TAILED) {
+        // exact cover by runs of P and P - 1 where the row is long enough for it
+        const int shorter = sh.runs * P - row_len;
+        if (shorter < sh.runs) sh.runs_full = sh.runs - shorter;
+    }
     sh.kgroups = (a.K + 63) / 64;
     long long ntiles = (long long)rows * sh.runs * sh.kgroups;
     if (ntiles > (1LL << 30)) return EBS_ERR_UNSUPPORTED;
@@ -510,7 +576,7 @@ static int launch_lane_cfg(const ConvArgs &a)
     // one generation of resident waves of a die: 32 compute units x 4 SIMDs x 8 waves
     sh.touch_ahead_pos = (dev->cus / 8 * 32 / (SPLIT ? 4 : 1) + sh.kgroups - 1) / sh.kgroups;
     sh.touch_ahead = sh.touch_ahead_pos * sh.kgroups;
-    hipLaunchKernelGGL((bd_conv_lane<KW, KA, P, ST, FS, REQ, SPLIT>), dim3((unsigned)(sh.xcd_chunk * 8)), dim3(256), 0, a.stream,
+    hipLaunchKernelGGL((bd_conv_lane<KW, KA, P, ST, FS, REQ, SPLIT, TAILED>), dim3((unsigned)(sh.xcd_chunk * 8)), dim3(256), 0, a.stream,
                        a.act, a.wgt, a.scale, a.offset, a.acc, a.out, a.next, sh);
     return hip_ok(hipGetLastError());
 }
@@ -522,7 +588,10 @@ static int launch_lane_fs(const ConvArgs &a, int sel)
     if (sel == 2) {
         if (a.stride == 1) return launch_lane_cfg<KW, KA, LaneRun<KW, KA, 1, FS>::SMALL, 1, FS, REQ, true>(a);
         if constexpr (FS == 3) {
-            if (a.stride == 2) return launch_lane_cfg<KW, KA, LaneRun<KW, KA, 2, FS>::BIG, 2, FS, REQ, true>(a);
+            if (a.stride == 2) {
+                using R = LaneRun<KW, KA, 2, FS>;
+                return launch_lane_cfg<KW, KA, R::BIG, 2, FS, REQ, true, R::TAILED>(a);
+            }
         }
         return EBS_ERR_UNSUPPORTED;
     }
@@ -531,8 +600,9 @@ static int launch_lane_fs(const ConvArgs &a, int sel)
         return launch_lane_cfg<KW, KA, LaneRun<KW, KA, 1, FS>::SMALL, 1, FS, REQ>(a);
     }
     if (a.stride == 2) {
-        if (sel == 0) return launch_lane_cfg<KW, KA, LaneRun<KW, KA, 2, FS>::BIG, 2, FS, REQ>(a);
-        return launch_lane_cfg<KW, KA, LaneRun<KW, KA, 2, FS>::SMALL, 2, FS, REQ>(a);
+        using R = LaneRun<KW, KA, 2, FS>;
+        if (sel == 0) return launch_lane_cfg<KW, KA, R::BIG, 2, FS, REQ, false, R::TAILED>(a);
+        return launch_lane_cfg<KW, KA, R::SMALL, 2, FS, REQ, false, R::TAILED>(a);
     }
     return EBS_ERR_UNSUPPORTED;
 }

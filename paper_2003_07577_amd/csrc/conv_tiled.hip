@@ -170,7 +170,7 @@ static int lane_choice(const ConvArgs &a)
 // positions and at least 256 input channels, where a wave of the unsplit kernel is one long chain of dependent
 // steps.  Measured on the ResNet-18 shapes against the choice below it: 512 @7x7 -3..-9 % up to six plane pairs
 // and at (3,3), +-1 % at eight and sixteen; 256->512 @14x14 stride 2 -7..-9 % with one- or two-bit activations
-// (runs of seven positions; equal at (1,1)), +3..+8 % with more (runs of four recompute an eighth of the row).
+// (runs of seven positions; equal at (1,1)).
 static bool split_choice(const ConvArgs &a)
 {
     const long long positions = (long long)a.N * a.OH * a.OW;
@@ -189,7 +189,10 @@ static bool split_choice(const ConvArgs &a)
     // (re-quantising: the tiled kernels that split the reduction are slower than their plain forms, 230 vs 199 us
     // on 512 @7x7 at (4,4), so there all pairs)
     if (a.stride == 1) return a.next || pairs <= 6 || pairs == 9;
-    if (a.stride == 2) return a.ka <= 2 && pairs >= 2;
+    // (three- and four-bit activations: runs of four and three positions that cover the row exactly; 256->512 @14x14
+    // stride 2: -4 % at (1,4) and (2,4), -9 % at (2,3), -7 % at (3,3) against the next best kernel, +1 % at (4,4);
+    // at (1,3) the unsplit kernel is 2 % faster)
+    if (a.stride == 2) return a.ka <= 2 ? pairs >= 2 : (pairs >= 4 && pairs < 16);
     return false;
 }
 

@@ -220,3 +220,35 @@ def test_random_deep_layers_forced_split_reduction(oracle_mod, block):
         assert np.array_equal(d["acc"].cpu().numpy(), ref), tag
         assert_f32_close(d["out"].cpu().numpy(), fref, ref, inp["scale"], inp["per_channel"])
     assert ran == 8
+
+
+@pytest.mark.parametrize("ka", [3, 4])
+def test_stride2_rows_of_every_length_forced_lane_kernels(oracle_mod, ka):
+    """Stride 2 with three- or four-bit activations: the channel-per-lane kernels cover an output row with runs of
+    four and three positions (a short run leaves its first position out), or move the last run left where the row
+    is too short for that.  Every row length from 4 to 17, unsplit and split reduction, both paddings."""
+    import torch
+    names = {ebs.ebs_conv_variant_name(v): v for v in range(ebs.ebs_conv_variant_count() + 1)}
+    for OW in range(4, 18):
+        pad = OW % 2
+        W = 2 * (OW - 1) + 3 - 2 * pad
+        kw = 1 + OW % 4
+        inp = wl.random_case(8800 + 20 * ka + OW, 2, 256, 7, W, 70, 3, 3, 2, pad, kw, ka, per_channel=bool(OW & 1),
+                             with_offset=True)
+        d = upload(inp, kw, ka, 2, pad)
+        pack(d)
+        g = d["g"]
+        assert g["OW"] == OW
+        ref = oracle_mod.conv2d_levels(inp["a"], inp["q"], 2, pad)
+        fref = oracle_mod.dequant(ref, inp["scale"], inp["offset"], inp["per_channel"])
+        for name in ("lane.small", "lane.split"):
+            print(f"[case] OW={OW} pad={pad} kw={kw} ka={ka} {name}", flush=True)
+            d["acc"].fill_(POISON)
+            d["out"].fill_(float("nan"))
+            rc = ebs.ebs_mixed_conv2d_variant(names[name], d["pa"], d["pw"], g["N"], g["C"], g["H"], g["W"], g["K"], 3, 3,
+                                              2, pad, kw, ka, d["scale"], d["offset"], d["per_channel"], d["acc"],
+                                              d["out"], check=False)
+            assert rc == 0, (OW, name, rc)
+            torch.cuda.synchronize()
+            assert np.array_equal(d["acc"].cpu().numpy(), ref), (OW, name)
+            assert_f32_close(d["out"].cpu().numpy(), fref, ref, inp["scale"], inp["per_channel"])

@@ -57,6 +57,7 @@ GEOS = [  # N, C, H, W, K, R, S, stride, pad
     (16, 256, 14, 14, 260, 3, 3, 1, 1),   # 3136 positions, eight words: lane kernel, reduction split among the waves
     (12, 256, 28, 28, 64, 3, 3, 2, 1),    # the same at stride 2 (runs of seven with one- or two-bit activations)
     (48, 512, 7, 7, 64, 1, 1, 1, 0),      # 1x1, sixteen words, 2352 positions: split as well
+    (44, 64, 28, 28, 64, 3, 3, 2, 1),     # stride 2, rows of 14 outputs: runs of 4 + 4 + 3 + 3 at three and four activation bits
 ]
 
 
