@@ -46,6 +46,7 @@ struct LaneShape {
     int touch_ahead;    // tiles between a tile and the one whose input it brings into the L2 (multiple of kgroups)
     int touch_ahead_pos;    // the same in position tiles (touch_ahead / kgroups)
     int per_channel;
+    int wtop;           // SGN kernels: 2^k_w - 1 (signed weights 2q - wtop, Eq. 1a)
     unsigned act_bytes, wgt_bytes;      // sizes of the packed operands
     FastDiv div_kgroups, div_runs, div_oh;
     // fused re-quantisation (REQ kernels): the next layer's quantiser and packed layout
@@ -128,7 +129,10 @@ template <int I, int N, class F> __device__ __forceinline__ void static_for(F &&
 // (14 = 4 + 4 + 3 + 3).  A short run is a run of P that starts one position early and leaves its first position
 // out: all its loads stay inside the row, and the arithmetic and the store of that position are skipped (one
 // wave-uniform branch per step).
-template <int KW, int KA, int P, int ST, int FS, bool REQ, bool SPLIT = false, bool TAILED = false>
+// SGN: signed weights 2q - (2^k_w - 1) (Eq. 1a): the result is 2 * sum(q*a) - (2^k_w - 1) * sum(a) over the window.
+// The window sums of the activation levels do not depend on the channel: each step's share is counted on the scalar
+// unit from the input piece the wave holds anyway.
+template <int KW, int KA, int P, int ST, int FS, bool REQ, bool SPLIT = false, bool TAILED = false, bool SGN = false>
 __global__ void __launch_bounds__(256)
 bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
              const float *__restrict__ scale, const float *__restrict__ offset,
@@ -138,7 +142,7 @@ bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
     constexpr int NCLS = KW + KA - 1;
     constexpr bool IMG = ST == 0;                 // runs over images (1x1 filter, one output position per image)
     static_assert(!IMG || (FS == 1 && SPLIT), "image runs: 1x1 filters, split reduction");
-    static_assert(!IMG || !REQ, "image runs: plain outputs");
+    static_assert(!IMG || (!REQ && !SGN), "image runs: plain outputs, unsigned weights");
     constexpr int XST = IMG ? 1 : ST;             // distance of consecutive positions in a step's registers
     constexpr int NSEG = (P - 1) * XST + FS;      // input positions one filter row of the run touches
     constexpr int XN = NSEG * KA;                 // dwords of one step's input piece
@@ -294,13 +298,18 @@ bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
         const uint64_t base = ((uint64_t)(uint32_t)uni((int)rq_base_hi) << 32) | (uint32_t)uni((int)rq_base_lo);
         return raw_buffer(reinterpret_cast<const void *>(base), (unsigned)uni((int)rq_span));
     };
+    // SGN: lane e (< XN) also reads word e of every step's input piece (see the window sums below)
+    static_assert(!SGN || XN <= 64, "one lane per word of the input piece");
+    const unsigned xv_lane = lane < (unsigned)XN ? lane4 : 0x80000000u;      // beyond any descriptor: reads 0
+    const unsigned xv_shift = lane % KA;                                     // the lane's plane
     int w_next = w0;                              // word index of the step the offsets point at
     int left = my_steps;                          // steps not yet requested
     // request the operands of the step the offsets point at (one scalar piece of input, one per-lane load per
     // tap that brings the k_w planes), then move the offsets one step on - without a branch, so that the loop
     // body stays one block of instructions; past the last step the offsets stay where they are
-    auto issue = [&](uint32_t (&x)[XN], uint32_t (&q)[FS][KW]) {
+    auto issue = [&](uint32_t (&x)[XN], uint32_t (&q)[FS][KW], uint32_t &xv) {
         const uint32_t *xs = act + x_off;         // wave-uniform address: scalar loads
+        if constexpr (SGN) xv = __builtin_amdgcn_raw_buffer_load_b32(abuf, (int)xv_lane, (int)(x_off * 4u), 0);
         if constexpr (IMG) {
 #pragma unroll
             for (int p = 0; p < P; ++p)
@@ -319,6 +328,31 @@ bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
         q_off += more ? (wrap ? q_rwrap : (unsigned)QSTEP) : 0u;
     };
 
+    // SGN: the window sums of the activation levels.  Besides the scalar loads, lane e (< XN) reads word e of every
+    // step's input piece with a vector load and keeps a running sum of its bitcounts, weighted by its plane; what
+    // a position's window holds is put together from those lanes once, after the reduction.  (Counting on the
+    // scalar unit from the piece in scalar registers was tried first: the temporaries did not fit beside the two
+    // input buffers.)
+    uint32_t level_sum = 0u;
+    auto window_sums = [&](uint32_t xv) {
+        if constexpr (SGN) level_sum += (uint32_t)__builtin_popcount(xv) << xv_shift;
+    };
+    // (2^k_w - 1) * sum of the levels in the window of each position (wave-uniform; after the reduction)
+    uint32_t wterm[P];
+    auto window_terms = [&]() {
+        if constexpr (SGN) {
+            uint32_t column = level_sum;             // lane c * k_a: sum over the planes of input column c
+#pragma unroll
+            for (int j = 1; j < KA; ++j) column += __shfl_down(level_sum, j);
+            uint32_t window = column;                // lane c * k_a: sum over the FS columns from c on
+#pragma unroll
+            for (int f = 1; f < FS; ++f) window += __shfl_down(column, f * KA);
+#pragma unroll
+            for (int p = 0; p < P; ++p)
+                wterm[p] = (uint32_t)__builtin_amdgcn_readlane((int)window, p * XST * KA) * (uint32_t)sh.wtop;
+        }
+    };
+    auto window_term = [&](int p) { return SGN ? wterm[p] : 0u; };
     uint32_t cls[P][NCLS];
     if constexpr (TAILED) {
         // (a position that is left out is never accumulated: give its registers a value)
@@ -327,8 +361,9 @@ bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
     }
     // Eq. 2 / Eq. 13 on one (filter row, word): the taps of the row for the P positions.  The very first step
     // writes every accumulator before it adds to it (shift class c first occurs at tap 0 with the smallest i).
-    auto mac = [&](const uint32_t (&x)[XN], const uint32_t (&q)[FS][KW], auto first_step) {
+    auto mac = [&](const uint32_t (&x)[XN], const uint32_t (&q)[FS][KW], uint32_t xv, auto first_step) {
         constexpr bool FIRST = decltype(first_step)::value;
+        window_sums(xv);
         auto position = [&](auto pc) {
             constexpr int p = decltype(pc)::value;
 #pragma unroll
@@ -373,32 +408,34 @@ bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
     // (requested one step ago), then requests the next step's, then multiplies: the wait the multiplication needs
     // would otherwise also cover the request just made.
     uint32_t xa[XN], xb[XN], qa[FS][KW], qb[FS][KW];
+    uint32_t va = 0u, vb = 0u;                    // SGN: the lanes' words of the two pieces
     const int trips = my_steps >> 1;
-    issue(xa, qa);
+    issue(xa, qa, va);
     __builtin_amdgcn_s_waitcnt(0xC07F);           // lgkmcnt(0)
     __builtin_amdgcn_sched_barrier(0);
-    issue(xb, qb);
+    issue(xb, qb, vb);
     __builtin_amdgcn_sched_barrier(0);
-    mac(xa, qa, first_t{});
+    mac(xa, qa, va, first_t{});
     __builtin_amdgcn_sched_barrier(0);
     for (int t = 1; t < trips; ++t) {
         __builtin_amdgcn_s_waitcnt(0xC07F);
         __builtin_amdgcn_sched_barrier(0);
-        issue(xa, qa);
+        issue(xa, qa, va);
         __builtin_amdgcn_sched_barrier(0);
-        mac(xb, qb, later_t{});
+        mac(xb, qb, vb, later_t{});
         __builtin_amdgcn_sched_barrier(0);
         __builtin_amdgcn_s_waitcnt(0xC07F);
         __builtin_amdgcn_sched_barrier(0);
-        issue(xb, qb);
+        issue(xb, qb, vb);
         __builtin_amdgcn_sched_barrier(0);
-        mac(xa, qa, later_t{});
+        mac(xa, qa, va, later_t{});
         __builtin_amdgcn_sched_barrier(0);
     }
     __builtin_amdgcn_s_waitcnt(0xC07F);
     __builtin_amdgcn_sched_barrier(0);
-    mac(xb, qb, later_t{});
+    mac(xb, qb, vb, later_t{});
 
+    window_terms();
     // (keeps the touching loads)
     if (touch_own) {
 #pragma unroll
@@ -419,6 +456,7 @@ bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
             uint32_t v = cls[p][0];
 #pragma unroll
             for (int c = 1; c < NCLS; ++c) v += cls[p][c] << c;
+            if constexpr (SGN) v = 2u * v - window_term(p);
             requant_store(p, v, nbuf, k_next);
         }
         return;
@@ -432,6 +470,7 @@ bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
             uint32_t v = 0;
 #pragma unroll
             for (int c = 0; c < NCLS; ++c) v += cls[p][c] << c;
+            if constexpr (SGN) v = 2u * v - window_term(p);    // linear: holds for the quarters' partial sums
             part[wave][p][lane] = v;
         }
         __syncthreads();
@@ -476,6 +515,7 @@ bd_conv_lane(const uint32_t *__restrict__ act, const uint32_t *__restrict__ wgt,
             uint32_t v = 0;
 #pragma unroll
             for (int c = 0; c < NCLS; ++c) v += cls[p][c] << c;
+            if constexpr (SGN) v = 2u * v - window_term(p);
             acc[p] = (int32_t)v;
         }
         // descriptors that start at the wave's first output value and end after its last one (the range check
@@ -512,11 +552,11 @@ template <int KW, int KA, int ST, int FS = 3> struct LaneRun {
     static constexpr bool TAILED = ST == 2 && KA >= 3;
 };
 
-template <int KW, int KA, int P, int ST, int FS, bool REQ, bool SPLIT = false, bool TAILED = false>
+template <int KW, int KA, int P, int ST, int FS, bool REQ, bool SPLIT = false, bool TAILED = false, bool SGN = false>
 static int launch_lane_cfg(const ConvArgs &a)
 {
     constexpr bool IMG = ST == 0;       // runs over images: one output position per image
-    if (a.wtop || (a.next != nullptr) != REQ) return EBS_ERR_UNSUPPORTED;
+    if ((a.wtop != 0) != SGN || (a.next != nullptr) != REQ) return EBS_ERR_UNSUPPORTED;
     if (a.R != FS || a.S != FS || a.pad > kActBorder) return EBS_ERR_UNSUPPORTED;
     if (IMG ? (a.OH != 1 || a.OW != 1 || a.N < P) : (a.stride != ST || a.OW < P)) return EBS_ERR_UNSUPPORTED;
     // image runs: the batch is described to the kernel as one output row of N positions
@@ -544,6 +584,7 @@ static int launch_lane_cfg(const ConvArgs &a)
     if (ntiles > (1LL << 30)) return EBS_ERR_UNSUPPORTED;
     sh.ntiles = (int)ntiles;
     sh.per_channel = a.per_channel;
+    sh.wtop = a.wtop;
     const size_t act_bytes = (size_t)sh.total_pos * a.cw * KA * sizeof(uint32_t);
     const size_t wgt_bytes = (size_t)((a.K + kWgtGroup - 1) / kWgtGroup) * kWgtGroup * FSZ * a.cw * KW * sizeof(uint32_t);
     if (act_bytes >= (1ull << 31) || wgt_bytes >= (1ull << 31)) return EBS_ERR_UNSUPPORTED;   // 32-bit byte offsets
@@ -576,33 +617,31 @@ static int launch_lane_cfg(const ConvArgs &a)
     // one generation of resident waves of a die: 32 compute units x 4 SIMDs x 8 waves
     sh.touch_ahead_pos = (dev->cus / 8 * 32 / (SPLIT ? 4 : 1) + sh.kgroups - 1) / sh.kgroups;
     sh.touch_ahead = sh.touch_ahead_pos * sh.kgroups;
-    hipLaunchKernelGGL((bd_conv_lane<KW, KA, P, ST, FS, REQ, SPLIT, TAILED>), dim3((unsigned)(sh.xcd_chunk * 8)), dim3(256), 0, a.stream,
+    hipLaunchKernelGGL((bd_conv_lane<KW, KA, P, ST, FS, REQ, SPLIT, TAILED, SGN>), dim3((unsigned)(sh.xcd_chunk * 8)), dim3(256), 0, a.stream,
                        a.act, a.wgt, a.scale, a.offset, a.acc, a.out, a.next, sh);
     return hip_ok(hipGetLastError());
 }
 
 // sel: 0 = large runs, 1 = small runs, 2 = small runs with the reduction split among a work-group's waves
-template <int KW, int KA, int FS, bool REQ>
+template <int KW, int KA, int FS, bool REQ, bool SGN = false>
 static int launch_lane_fs(const ConvArgs &a, int sel)
 {
+    using R1 = LaneRun<KW, KA, 1, FS>;
+    using R2 = LaneRun<KW, KA, 2, FS>;
     if (sel == 2) {
-        if (a.stride == 1) return launch_lane_cfg<KW, KA, LaneRun<KW, KA, 1, FS>::SMALL, 1, FS, REQ, true>(a);
+        if (a.stride == 1) return launch_lane_cfg<KW, KA, R1::SMALL, 1, FS, REQ, true, false, SGN>(a);
         if constexpr (FS == 3) {
-            if (a.stride == 2) {
-                using R = LaneRun<KW, KA, 2, FS>;
-                return launch_lane_cfg<KW, KA, R::BIG, 2, FS, REQ, true, R::TAILED>(a);
-            }
+            if (a.stride == 2) return launch_lane_cfg<KW, KA, R2::BIG, 2, FS, REQ, true, R2::TAILED, SGN>(a);
         }
         return EBS_ERR_UNSUPPORTED;
     }
     if (a.stride == 1) {
-        if (sel == 0) return launch_lane_cfg<KW, KA, LaneRun<KW, KA, 1, FS>::BIG, 1, FS, REQ>(a);
-        return launch_lane_cfg<KW, KA, LaneRun<KW, KA, 1, FS>::SMALL, 1, FS, REQ>(a);
+        if (sel == 0) return launch_lane_cfg<KW, KA, R1::BIG, 1, FS, REQ, false, false, SGN>(a);
+        return launch_lane_cfg<KW, KA, R1::SMALL, 1, FS, REQ, false, false, SGN>(a);
     }
     if (a.stride == 2) {
-        using R = LaneRun<KW, KA, 2, FS>;
-        if (sel == 0) return launch_lane_cfg<KW, KA, R::BIG, 2, FS, REQ, false, R::TAILED>(a);
-        return launch_lane_cfg<KW, KA, R::SMALL, 2, FS, REQ, false, R::TAILED>(a);
+        if (sel == 0) return launch_lane_cfg<KW, KA, R2::BIG, 2, FS, REQ, false, R2::TAILED, SGN>(a);
+        return launch_lane_cfg<KW, KA, R2::SMALL, 2, FS, REQ, false, R2::TAILED, SGN>(a);
     }
     return EBS_ERR_UNSUPPORTED;
 }
@@ -619,6 +658,11 @@ template <int KW, int KA>
 static int launch_lane_pair_impl(const ConvArgs &a, int sel)
 {
     if (!a.next && a.R == 1 && a.S == 1 && a.OH == 1 && a.OW == 1) return launch_lane_images<KW, KA>(a, sel);
+    // signed weights: the 3x3 kernels only
+    if (a.wtop) {
+        if (a.R != 3 || a.S != 3) return EBS_ERR_UNSUPPORTED;
+        return a.next ? launch_lane_fs<KW, KA, 3, true, true>(a, sel) : launch_lane_fs<KW, KA, 3, false, true>(a, sel);
+    }
     if (a.next) {
         if (a.R == 3 && a.S == 3) return launch_lane_fs<KW, KA, 3, true>(a, sel);
         if (a.R == 1 && a.S == 1) return launch_lane_fs<KW, KA, 1, true>(a, sel);

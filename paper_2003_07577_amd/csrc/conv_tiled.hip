@@ -109,7 +109,7 @@ static int lane_choice(const ConvArgs &a)
     // reductions - and loses on the deepest stride-1 layer (few positions: too few tiles), at the highest
     // bitwidths of the layers with many positions, and when many of a wave's 64 channel lanes would idle.
     // Measured on the ResNet-18 shapes, all 16 pairs, both kernels forced in turn.
-    if (rs == 9 && a.R == 3 && a.kw <= 4 && a.ka <= 4 && !a.wtop && (a.cw & 1) == 0 && (a.K % 64 == 0 || a.K >= 256)) {
+    if (rs == 9 && a.R == 3 && a.kw <= 4 && a.ka <= 4 && (a.cw & 1) == 0 && (a.K % 64 == 0 || a.K >= 256)) {
         const int pairs = a.kw * a.ka;
         bool use = false;
         if (positions >= 8192) {
@@ -124,6 +124,8 @@ static int lane_choice(const ConvArgs &a)
         // the highest bitwidths; the lane kernel pays 2-3 % for its epilogue (measured: (4,4) -4..-6 % on 128 @28x28,
         // 64->128 @56x56 s2, 256->512 @14x14 s2; stride 2 at (3,3)/(4,3) -2..-5 %; (3,4) +-3 %, left alone)
         if (a.next && positions >= 3072 && (pairs == 16 || (a.stride == 2 && a.ka == 3 && a.kw >= 3))) use = true;
+        // (signed weights cost the tiled kernels another 8 % there: (3,4) on 128 @28x28 156 vs 167 us; stride 2: equal)
+        if (a.next && a.wtop && positions >= 3072 && a.stride == 1) use = true;
         if (use) {
             // small runs where the large ones leave fewer than six tiles per SIMD and divide the row
             const int big = lane_run_length(a.kw, a.ka, a.stride, a.R, 0), small = lane_run_length(a.kw, a.ka, a.stride, a.R, 1);
@@ -175,7 +177,7 @@ static bool split_choice(const ConvArgs &a)
 {
     const long long positions = (long long)a.N * a.OH * a.OW;
     const int pairs = a.kw * a.ka;
-    if (a.wtop || a.R != a.S || (a.R != 3 && a.R != 1) || a.kw > 4 || a.ka > 4 || (a.cw & 7) || a.R * a.cw > 256)
+    if ((a.wtop && a.R != 3) || a.R != a.S || (a.R != 3 && a.R != 1) || a.kw > 4 || a.ka > 4 || (a.cw & 7) || a.R * a.cw > 256)
         return false;
     if (positions < 2048 || (a.K % 64 != 0 && a.K < 256)) return false;
     const int run = lane_run_length(a.kw, a.ka, a.stride, a.R, a.stride == 1 ? 1 : 0);
@@ -207,12 +209,12 @@ int launch_requant_tiled(const ConvArgs &a)
         const int rc = launch_conv_pair(a);
         if (rc != EBS_ERR_UNSUPPORTED) return rc;
     }
-    // the channel-per-lane kernel where the plain convolution would use it (unsigned weights only)
+    // the channel-per-lane kernel where the plain convolution would use it
     if (split_choice(a)) {
         const int rc = launch_conv_lane(a, 2);
         if (rc != EBS_ERR_UNSUPPORTED) return rc;
     }
-    if (!a.wtop) {
+    {
         const int sel = lane_choice(a);
         if (sel >= 0) {
             int rc = launch_conv_lane(a, sel);

@@ -20,6 +20,14 @@ GEOS = [  # N, C, H, W, K, R, S, stride, pad
     (3, 16, 12, 10, 16, 3, 3, 1, 1),       # 16 input channels -> two taps per word, window sums from the pair words
     (2, 12, 9, 11, 20, 3, 3, 2, 1),        # the same, ragged C and K, stride 2
 ]
+# shapes the heuristic sends to the channel-per-lane kernels (window sums counted on the scalar unit)
+LANE_GEOS = [
+    (8, 64, 40, 28, 128, 3, 3, 1, 1),      # 8960 positions, runs of 14 / 7
+    (16, 64, 48, 56, 64, 3, 3, 2, 1),      # stride 2, rows of 28 outputs
+    (44, 64, 28, 28, 64, 3, 3, 2, 1),      # stride 2, rows of 14 outputs: short runs at three and four activation bits
+    (16, 256, 14, 14, 260, 3, 3, 1, 1),    # 3136 positions, eight words: reduction split among the waves, K ragged
+    (12, 256, 28, 28, 64, 3, 3, 2, 1),     # the same at stride 2
+]
 
 
 @pytest.mark.parametrize("kw,ka", wl.PAPER_BITS)
@@ -83,3 +91,40 @@ def test_signed_requant_full_layer(oracle_mod):
     assert np.array_equal(lv, ref)
     assert ref.min() == 0 and ref.max() >= 8         # the case spans a wide range of levels
     assert not padbits.any() and not border.any()
+
+
+@pytest.mark.parametrize("kw,ka", [(1, 1), (2, 2), (4, 2), (1, 4), (3, 3), (2, 4), (4, 4), (3, 1)])
+def test_signed_lane_shapes_plain_and_requant(oracle_mod, kw, ka):
+    """Signed weights on the shapes that take the channel-per-lane kernels: int32 accumulators bit-exact, and the
+    fused re-quantising call's levels, zero ring and padding bits."""
+    import torch
+    for gi, (N, C, H, W, K, R, S, st, pad) in enumerate(LANE_GEOS):
+        inp = wl.random_case(8600 + 20 * gi + 4 * kw + ka, N, C, H, W, K, R, S, st, pad, kw, ka,
+                             per_channel=(gi % 2 == 0), with_offset=True)
+        print(f"[case] signed lane geo{gi} kw={kw} ka={ka}", flush=True)
+        d = upload(inp, kw, ka, st, pad)
+        pack(d)
+        g = d["g"]
+        geo = (g["N"], g["C"], g["H"], g["W"], g["K"], g["R"], g["S"], st, pad, kw, ka)
+        ebs.ebs_mixed_conv2d_signed(d["pa"], d["pw"], *geo, d["scale"], d["offset"], d["per_channel"], d["acc"], d["out"])
+        torch.cuda.synchronize()
+        ref = oracle_mod.conv2d_signed_levels(inp["a"], inp["q"], kw, st, pad)
+        acc = d["acc"].cpu().numpy()
+        assert np.array_equal(acc, ref), (gi, kw, ka, int((acc != ref).sum()))
+        fref = oracle_mod.dequant(ref, inp["scale"], inp["offset"], inp["per_channel"])
+        assert_f32_close(d["out"].cpu().numpy(), fref, ref, inp["scale"], inp["per_channel"])
+        # fused re-quantisation: spread the outputs over and beyond the clip range
+        top = C * R * S * (2 ** kw - 1) * (2 ** ka - 1)
+        sc = (inp["scale"] * np.float32(40.0 / top)).astype(np.float32)
+        of = (inp["offset"] * np.float32(4.0) + np.float32(1.0)).astype(np.float32)
+        k_next, alpha = 1 + (gi + kw) % 5, 6.0
+        nxt = torch.full((ebs.ebs_packed_activations_bytes(N, g["OH"], g["OW"], K, k_next) // 4,), POISON,
+                         dtype=torch.int32, device=d["acc"].device)
+        ebs.ebs_mixed_conv2d_requant(d["pa"], d["pw"], *geo, torch.from_numpy(sc).to(nxt.device),
+                                     torch.from_numpy(of).to(nxt.device), inp["per_channel"], alpha, k_next, nxt,
+                                     signed_weights=True)
+        torch.cuda.synchronize()
+        want = oracle_mod.requant_levels(ref, sc, of, inp["per_channel"], alpha, k_next)
+        lv, padbits, border = unpack_activations(nxt.cpu().numpy(), N, g["OH"], g["OW"], K, k_next)
+        assert np.array_equal(lv, want), (gi, kw, ka)
+        assert not padbits.any() and not border.any(), (gi, kw, ka)
